@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark: one MoE layer forward (route -> permute -> gate+up -> down -> combine) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral] [--T 512]
+
+Prints ONE JSON line.  `value` is tokens/s of the whole layer with all inputs resident in HBM.
+`roofline` is for the dominant kernel (the fused gate+up grouped GEMM), timed inside the timed
+region with HIP events recorded by the library on the launch stream.  `cpu_baseline` is the
+fp64 numpy oracle timed on this machine's host cores on a bounded token sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import moe_inputs as mi  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA peak
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default="mixtral", choices=sorted(mi.PRESETS))
+    ap.add_argument("--T", type=int, default=512)
+    ap.add_argument("--skew", type=float, default=0.0)
+    ap.add_argument("--tile-m", type=int, default=0)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle's FFN is timed on (0 = auto)")
+    return ap.parse_args()
+
+
+def cpu_baseline(shape, x_cpu, wr_cpu, bias_cpu, seed, sample):
+    """The oracle as it stands: routing + permutation on all T tokens, FFN on `sample` tokens."""
+    from oracle import moe_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    rng = np.random.default_rng(seed + 17)
+    tokens = sorted(rng.choice(shape.T, size=min(sample, shape.T), replace=False).tolist())
+    prov = lambda e: tuple(mi.bits(t) for t in mi.make_expert(shape, e, seed))
+    t0 = time.perf_counter()
+    out = orc.moe_forward(mi.bits(x_cpu), mi.bits(wr_cpu), None if bias_cpu is None else bias_cpu.numpy(), prov,
+                          shape.k, shape.gating, tokens=tokens)
+    dt = time.perf_counter() - t0
+    return {"value": len(tokens) / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"fp64 numpy oracle: routing+permutation of all {shape.T} tokens, expert FFN+combine of "
+                      f"{len(tokens)} seeded tokens ({dt:.1f} s, includes regenerating and decoding the experts hit)"}, out
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no expert sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    import paper_2605_23911_amd as moe
+    moe.lib()   # raises if the HIP library has not been built: there is no fallback
+
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    s = mi.PRESETS[args.config].with_T(args.T)
+    x_cpu, wr_cpu = mi.make_x(s, args.seed), mi.make_router(s, args.seed)
+    bias_cpu = mi.skew_bias(s, args.skew, args.seed)
+    x, wr = x_cpu.to(dev), wr_cpu.to(dev)
+    bias = None if bias_cpu is None else bias_cpu.to(dev)
+    wg = torch.empty((s.E, s.F, s.d), dtype=torch.bfloat16, device=dev)
+    wu = torch.empty((s.E, s.F, s.d), dtype=torch.bfloat16, device=dev)
+    wd = torch.empty((s.E, s.d, s.F), dtype=torch.bfloat16, device=dev)
+    mi.make_all_experts(s, args.seed, out=(wg, wu, wd))
+    cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating, args.tile_m)
+    lay = moe.forward_workspace_layout(cfg)
+    ws = torch.zeros(lay.total, dtype=torch.uint8, device=dev)
+    y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def new_event():
+        ev = torch.cuda.Event(enable_timing=True)
+        ev.record(stream)          # creates the underlying hipEvent_t; the library re-records it
+        return ev
+
+    for _ in range(args.warmup):
+        moe.moe_forward(cfg, x, wr, bias, wg, wu, wd, y, ws)
+    torch.cuda.synchronize()
+
+    # ---- timed region: K steps; events [2] and [3] bracket the gate+up kernel of every step
+    K = args.steps
+    ev_a = [new_event() for _ in range(K)]
+    ev_b = [new_event() for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws,
+                               [None, None, ev_a[i].cuda_event, ev_b[i].cuda_event, None, None])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    gate_up_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev_a, ev_b)]))
+
+    # ---- per-stage breakdown (outside the timed region)
+    evs = [[new_event() for _ in range(6)] for _ in range(10)]
+    torch.cuda.synchronize()
+    for row in evs:
+        moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws, [e.cuda_event for e in row])
+    torch.cuda.synchronize()
+    names = ["route", "permute", "gate_up", "down", "combine"]
+    stages = {n: float(np.median([row[i].elapsed_time(row[i + 1]) for row in evs])) for i, n in enumerate(names)}
+    stages["total_events"] = float(np.median([row[0].elapsed_time(row[5]) for row in evs]))
+
+    # ---- algorithmic work from the actual routing
+    counts = ws[lay.counts: lay.counts + 4 * s.E].view(torch.int32).cpu().numpy()
+    e_active = int((counts > 0).sum())
+    R = s.R
+    gate_up_bytes = 4 * s.d * s.F * e_active + 2 * R * s.d + 2 * R * s.F       # weights once, x_perm in, h out
+    gate_up_flops = 4 * R * s.d * s.F
+    layer_bytes = (6 * s.d * s.F * e_active + 2 * s.E * s.d + 2 * s.T * s.d + 2 * 2 * R * s.d + 2 * 2 * R * s.F
+                   + 2 * 2 * R * s.d + 2 * s.T * s.d + 16 * R)
+    layer_flops = s.T * (6 * s.k * s.d * s.F + 2 * s.E * s.d)
+    mean_rows = R / max(e_active, 1)
+    if mean_rows > 312:      # ridge point 2.5 PFLOP/s / 8 TB/s
+        ach = gate_up_flops / (gate_up_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None}
+    else:
+        ach = gate_up_bytes / (gate_up_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": ach / HBM_PEAK_GBS, "traffic": None}
+    roofline.update({"kernel": "grouped_gemm_kernel<gate+up>", "kernel_ms": gate_up_ms,
+                     "algorithmic_bytes": gate_up_bytes, "algorithmic_flops": gate_up_flops,
+                     "active_experts": e_active})
+
+    result = {
+        "metric": "moe_layer_forward_tokens_per_s", "value": s.T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{s.name}-shaped MoE layer forward, T={s.T} tokens, d={s.d}, F={s.F}, E={s.E}, "
+                               f"top-k={s.k}, gating={s.gating}, skew={args.skew}, seed={args.seed}",
+                   "tile_m": moe.tile_m(cfg)},
+        "roofline": roofline,
+        "layer": {"hbm_frac": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                  "mfma_frac": layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                  "algorithmic_bytes": layer_bytes, "algorithmic_flops": layer_flops},
+        "stages_ms": stages,
+    }
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample or 8
+        result["cpu_baseline"], ref = cpu_baseline(s, x_cpu, wr_cpu, bias_cpu, args.seed, sample)
+        yb = y.cpu().view(torch.int16).numpy().view(np.uint16)[ref["tokens"]]
+        yg = (yb.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+        result["parity_max_rel_err_sampled"] = float(np.abs(yg - ref["y"]).max() / np.abs(ref["y"]).max())
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,158 @@
+/*
+ * moe.h - C ABI of the MI355X (gfx950) MoE-layer forward library.
+ *
+ * One Mixture-of-Experts layer, forward only, as defined in the paper's Sec. 2.1:
+ *   Eq. 1   s = softmax(W_r x)
+ *   Eq. 2   T = top-k(s) = {(e_i, w_i)}
+ *   Eq. 3   y = sum_i w_i * FFN_{e_i}(x)
+ *   Eq. 4   FFN_e(x) = (SiLU(x W_gate_e) (.) x W_up_e) W_down_e
+ * executed as the five stages of Sec. 3.1: route, permute into expert-contiguous
+ * order (Sec. 3.5), fused gate+up grouped GEMM (Sec. 3.2-3.3), down grouped GEMM,
+ * weighted un-permute / combine (Sec. 3.5, Eq. 3).
+ *
+ * Conventions common to every entry point
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library never
+ *     allocates, frees or keeps a pointer beyond the work it enqueues.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue kernels; they never synchronise.  The caller keeps all buffers alive until
+ *     the stream has drained.  No host<->device copy happens anywhere.
+ *   - bf16 tensors are uint16 bit patterns, row-major, base pointer 16-byte aligned.
+ *   - Stored weight matrices are [out, in] with the reduction dimension contiguous
+ *     (Sec. 3.2's "E*N x K" flattened layout): W_r [E,d], W_gate,W_up [E,F,d], W_down [E,d,F].
+ *     Eq. 4's "x W" is therefore x times the transpose of the stored matrix.
+ *   - Notation: T tokens, d model dim, F expert FFN dim, E experts, k experts per token,
+ *     R = T*k expanded rows, n_e rows routed to expert e.
+ *   - Limits: 1 <= k <= E <= 256, d % 64 == 0, F % 64 == 0, T >= 0, T*k*max(d,F) < 2^31 rows*cols
+ *     addressed with 64-bit offsets.  T == 0 returns MOE_OK and enqueues nothing.
+ *   - All argument checks run on the host before anything is enqueued: a call that returns
+ *     an error has had no effect on device memory.  Errors are return codes only.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_ERR_NULL = -1,        /* a required pointer is NULL */
+    MOE_ERR_SHAPE = -2,       /* T<0, k<1, k>E, E<1, d<1, F<1, unknown gating */
+    MOE_ERR_ALIGN = -3,       /* a tensor base pointer is not 16-byte aligned */
+    MOE_ERR_WORKSPACE = -4,   /* workspace smaller than the matching *_workspace_size() */
+    MOE_ERR_UNSUPPORTED = -5, /* E > 256, d % 64 != 0, F % 64 != 0, sizes beyond 32-bit rows */
+    MOE_ERR_HIP = -6          /* a kernel launch reported a HIP error */
+} moe_status;
+
+typedef enum {
+    MOE_GATE_SOFTMAX = 0,        /* w_i = softmax(z)[e_i]                      (Eq. 1-2) */
+    MOE_GATE_SOFTMAX_RENORM = 1, /* w_i = softmax(z)[e_i] / sum_j softmax(z)[e_j]        */
+    MOE_GATE_SIGMOID_NORM = 2    /* w_i = sigmoid(z_{e_i}) / sum_j sigmoid(z_{e_j})  (Sec. 3.4) */
+} moe_gating;
+
+typedef struct {
+    int32_t T, d, F, E, k;
+    int32_t gating;       /* moe_gating */
+    int32_t tile_m;       /* rows per block-schedule tile (Alg. 1's M); 0 = chosen from T*k/E */
+    int32_t reserved;     /* must be 0 */
+} moe_config;
+
+/* Byte offsets of moe_forward's intermediates inside its workspace (all 256-byte aligned). */
+typedef struct {
+    size_t topk_idx;  /* int32 [T,k] */
+    size_t topk_w;    /* float [T,k] */
+    size_t counts;    /* int32 [E]   */
+    size_t offsets;   /* int32 [E+1] */
+    size_t row_of;    /* int32 [R]   */
+    size_t src_of;    /* int32 [R]   */
+    size_t x_perm;    /* bf16  [R,d] */
+    size_t h;         /* bf16  [R,F] */
+    size_t y_perm;    /* bf16  [R,d] */
+    size_t scratch;   /* internal: chunk histograms, block schedule */
+    size_t total;     /* bytes needed */
+} moe_workspace_layout;
+
+const char* moe_status_string(moe_status s);
+
+/* Tile height (Alg. 1's M) the library uses for this config: cfg->tile_m if non-zero
+ * (must be 32, 64, 128 or 256), else picked from the mean rows per expert T*k/E.
+ * Returns 0 for an invalid config. */
+int32_t moe_tile_m(const moe_config* cfg);
+
+/* Workspace sizes in bytes (0 for an invalid config).  Host only, no GPU needed. */
+size_t moe_permute_workspace_size(const moe_config* cfg);
+size_t moe_ffn_workspace_size(const moe_config* cfg);
+size_t moe_forward_workspace_size(const moe_config* cfg);
+/* Fills *out with the layout moe_forward uses; returns MOE_OK or the config error. */
+moe_status moe_forward_workspace_layout(const moe_config* cfg, moe_workspace_layout* out);
+/* Upper bound on Alg. 1's block count for tile height M: floor(R/M) + min(E, R). */
+int32_t moe_max_blocks(const moe_config* cfg, int32_t M);
+
+/* Stage 1, router (Eq. 1-2, Sec. 3.4).
+ *   x [T,d] bf16, W_r [E,d] bf16, bias [E] fp32 or NULL (added to the logits)
+ *   -> topk_idx [T,k] int32, topk_w [T,k] fp32.
+ * Logits z = W_r x + bias are accumulated in fp64.  The k experts are chosen by k rounds
+ * of arg-max over z with the winner masked; a tie goes to the lower expert index; outputs
+ * are in selection order (descending score).  Weights follow cfg->gating. */
+moe_status moe_route(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
+                     int32_t* topk_idx, float* topk_w, void* stream);
+
+/* Stage 2, permutation into expert-contiguous order (Sec. 2.2, Sec. 3.5).
+ *   topk_idx [T,k] (any valid assignment: values in [0,E), as Sec. 4.7 injects them)
+ *   -> counts [E] (n_e), offsets [E+1] (exclusive prefix sum, offsets[E] = R),
+ *      row_of [R] (row of flat slot j = t*k+i after a STABLE sort by expert id),
+ *      src_of [R] (inverse: slot stored at row r), x_perm [R,d] = x[src_of[r]/k, :].
+ * x and x_perm may both be NULL to compute the index arrays only.
+ * An index outside [0,E) cannot be reported (that would need a device->host sync); it is
+ * clamped into [0,E-1], so every row index the kernels produce stays inside the buffers. */
+moe_status moe_permute(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                       int32_t* counts, int32_t* offsets, int32_t* row_of, int32_t* src_of,
+                       void* x_perm, void* workspace, size_t ws_bytes, void* stream);
+
+/* Alg. 1 on the device: blocks [max_blocks,2] int32 = (expert, b*M) in emission order,
+ * *num_blocks (device int32) = sum_e ceil(n_e/M).  Entries past *num_blocks are untouched.
+ * `blocks` must hold moe_max_blocks(cfg, M) pairs. */
+moe_status moe_block_schedule(const moe_config* cfg, const int32_t* offsets, int32_t M,
+                              int32_t* blocks, int32_t* num_blocks, void* stream);
+
+/* Stages 3+4, expert FFN as two block-scheduled grouped GEMMs (Sec. 3.2, 3.3, Eq. 4).
+ *   x_perm [R,d] bf16 expert-contiguous, offsets [E+1]
+ *   W_gate, W_up [E,F,d] bf16, W_down [E,d,F] bf16
+ *   -> h [R,F] bf16 = SiLU(x W_gate^T) (.) (x W_up^T)  (fp32 accumulate, SiLU and product in
+ *      fp32 registers, one rounding to bf16), y_perm [R,d] bf16 = h W_down^T (fp32 accumulate).
+ * The block schedule is built on the device from `offsets`; no host synchronisation. */
+moe_status moe_grouped_ffn(const moe_config* cfg, const void* x_perm, const int32_t* offsets,
+                           const void* W_gate, const void* W_up, const void* W_down,
+                           void* h, void* y_perm, void* workspace, size_t ws_bytes, void* stream);
+
+/* Stage 5, un-permute + weighted combine (Eq. 3, Sec. 3.5).
+ *   y[t,:] = sum_{i<k} topk_w[t,i] * y_perm[row_of[t*k+i], :], fp32 accumulation in slot
+ *   order, one rounding to bf16.  No atomics: results are bit-reproducible. */
+moe_status moe_combine(const moe_config* cfg, const void* y_perm, const int32_t* row_of,
+                       const float* topk_w, void* y, void* stream);
+
+/* The whole layer: stages 1-5 enqueued back to back on `stream`, intermediates in
+ * `workspace` at moe_forward_workspace_layout()'s offsets.  y [T,d] bf16. */
+moe_status moe_forward(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
+                       const void* W_gate, const void* W_up, const void* W_down,
+                       void* y, void* workspace, size_t ws_bytes, void* stream);
+
+/* moe_forward with timing hooks: `events` is an array of n_events hipEvent_t handles (as void*,
+ * entries may be NULL, the array itself may be NULL when n_events == 0) recorded on `stream`
+ *   [0] before the router, [1] after it, [2] after the permutation (index arrays + row gather),
+ *   [3] after the fused gate+up GEMM, [4] after the down GEMM, [5] after the combine.
+ * Entries beyond index 5 are ignored.  Everything else is exactly moe_forward (Sec. 3.1's
+ * five stages; the per-stage breakdown mirrors the paper's Table 6). */
+#define MOE_NUM_STAGE_EVENTS 6
+moe_status moe_forward_staged(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
+                              const void* W_gate, const void* W_up, const void* W_down,
+                              void* y, void* workspace, size_t ws_bytes, void* stream,
+                              void* const* events, int32_t n_events);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

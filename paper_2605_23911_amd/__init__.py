@@ -1,0 +1,29 @@
+"""MI355X-native MoE layer forward (route, permute, fused gate+up / down grouped GEMM, combine).
+
+The package is a thin ctypes binding over the C ABI declared in include/moe.h; every step of
+the path runs in the HIP library.  There is no CPU fallback: calling an entry point without
+the built library raises.
+"""
+from .binding import (  # noqa: F401
+    GATE_SIGMOID_NORM,
+    GATE_SOFTMAX,
+    GATE_SOFTMAX_RENORM,
+    MoEConfig,
+    MoEError,
+    WorkspaceLayout,
+    forward_workspace_layout,
+    forward_workspace_size,
+    ffn_workspace_size,
+    lib,
+    library_path,
+    max_blocks,
+    moe_block_schedule,
+    moe_combine,
+    moe_forward,
+    moe_forward_staged,
+    moe_grouped_ffn,
+    moe_permute,
+    moe_route,
+    permute_workspace_size,
+    tile_m,
+)

@@ -1,0 +1,180 @@
+"""ctypes binding of include/moe.h: argument marshalling only.
+
+Tensors are torch tensors on the GPU (torch is used for device memory and streams only);
+their data pointers and the current stream handle are passed straight to the C ABI.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch  # imported before the library so that both share one HIP runtime
+
+GATE_SOFTMAX = 0
+GATE_SOFTMAX_RENORM = 1
+GATE_SIGMOID_NORM = 2
+
+_LIB_NAME = "libmoe_mi355x.so"
+_lib = None
+
+EXPORTS = (
+    "moe_status_string", "moe_tile_m", "moe_permute_workspace_size", "moe_ffn_workspace_size",
+    "moe_forward_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
+    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged",
+)
+
+
+class MoEError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().moe_status_string(status).decode() if _lib is not None else str(status)
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class MoEConfig(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("F", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
+                ("gating", C.c_int32), ("tile_m", C.c_int32), ("reserved", C.c_int32)]
+
+    @classmethod
+    def of(cls, T, d, F, E, k, gating=GATE_SOFTMAX, tile_m=0):
+        return cls(T, d, F, E, k, gating, tile_m, 0)
+
+
+class WorkspaceLayout(C.Structure):
+    _fields_ = [(n, C.c_size_t) for n in ("topk_idx", "topk_w", "counts", "offsets", "row_of", "src_of",
+                                          "x_perm", "h", "y_perm", "scratch", "total")]
+
+
+def library_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), _LIB_NAME)
+
+
+def lib() -> C.CDLL:
+    """Load the HIP library (built in-tree by build.py).  No fallback: raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2605_23911_amd.build` "
+                           "(or __graft_entry__.build()); there is no CPU fallback")
+    L = C.CDLL(path)
+    cfgp, vp, i32p, f32p = C.POINTER(MoEConfig), C.c_void_p, C.c_void_p, C.c_void_p
+    L.moe_status_string.restype = C.c_char_p
+    L.moe_status_string.argtypes = [C.c_int]
+    L.moe_tile_m.restype = C.c_int32
+    L.moe_tile_m.argtypes = [cfgp]
+    L.moe_max_blocks.restype = C.c_int32
+    L.moe_max_blocks.argtypes = [cfgp, C.c_int32]
+    for n in ("moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size"):
+        getattr(L, n).restype = C.c_size_t
+        getattr(L, n).argtypes = [cfgp]
+    L.moe_forward_workspace_layout.restype = C.c_int
+    L.moe_forward_workspace_layout.argtypes = [cfgp, C.POINTER(WorkspaceLayout)]
+    L.moe_route.restype = C.c_int
+    L.moe_route.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, vp]
+    L.moe_permute.restype = C.c_int
+    L.moe_permute.argtypes = [cfgp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
+    L.moe_block_schedule.restype = C.c_int
+    L.moe_block_schedule.argtypes = [cfgp, i32p, C.c_int32, i32p, i32p, vp]
+    L.moe_grouped_ffn.restype = C.c_int
+    L.moe_grouped_ffn.argtypes = [cfgp, vp, i32p, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.moe_combine.restype = C.c_int
+    L.moe_combine.argtypes = [cfgp, vp, i32p, f32p, vp, vp]
+    L.moe_forward.restype = C.c_int
+    L.moe_forward.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.moe_forward_staged.restype = C.c_int
+    L.moe_forward_staged.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(C.c_void_p),
+                                     C.c_int32]
+    _lib = L
+    return L
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors handed to the MoE library must be contiguous GPU tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise MoEError(status, where)
+
+
+def _nbytes(t) -> int:
+    return t.numel() * t.element_size()
+
+
+def tile_m(cfg) -> int:
+    return lib().moe_tile_m(C.byref(cfg))
+
+
+def max_blocks(cfg, M: int) -> int:
+    return lib().moe_max_blocks(C.byref(cfg), M)
+
+
+def permute_workspace_size(cfg) -> int:
+    return lib().moe_permute_workspace_size(C.byref(cfg))
+
+
+def ffn_workspace_size(cfg) -> int:
+    return lib().moe_ffn_workspace_size(C.byref(cfg))
+
+
+def forward_workspace_size(cfg) -> int:
+    return lib().moe_forward_workspace_size(C.byref(cfg))
+
+
+def forward_workspace_layout(cfg) -> WorkspaceLayout:
+    out = WorkspaceLayout()
+    _check(lib().moe_forward_workspace_layout(C.byref(cfg), C.byref(out)), "moe_forward_workspace_layout")
+    return out
+
+
+def moe_route(cfg, x, W_r, bias, topk_idx, topk_w, stream=None):
+    _check(lib().moe_route(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(topk_idx), _ptr(topk_w),
+                           _stream(stream)), "moe_route")
+
+
+def moe_permute(cfg, x, topk_idx, counts, offsets, row_of, src_of, x_perm, workspace, stream=None):
+    _check(lib().moe_permute(C.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(row_of),
+                             _ptr(src_of), _ptr(x_perm), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "moe_permute")
+
+
+def moe_block_schedule(cfg, offsets, M, blocks, num_blocks, stream=None):
+    _check(lib().moe_block_schedule(C.byref(cfg), _ptr(offsets), M, _ptr(blocks), _ptr(num_blocks),
+                                    _stream(stream)), "moe_block_schedule")
+
+
+def moe_grouped_ffn(cfg, x_perm, offsets, W_gate, W_up, W_down, h, y_perm, workspace, stream=None):
+    _check(lib().moe_grouped_ffn(C.byref(cfg), _ptr(x_perm), _ptr(offsets), _ptr(W_gate), _ptr(W_up),
+                                 _ptr(W_down), _ptr(h), _ptr(y_perm), _ptr(workspace), _nbytes(workspace),
+                                 _stream(stream)), "moe_grouped_ffn")
+
+
+def moe_combine(cfg, y_perm, row_of, topk_w, y, stream=None):
+    _check(lib().moe_combine(C.byref(cfg), _ptr(y_perm), _ptr(row_of), _ptr(topk_w), _ptr(y), _stream(stream)),
+           "moe_combine")
+
+
+def moe_forward(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, stream=None):
+    _check(lib().moe_forward(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(W_gate), _ptr(W_up),
+                             _ptr(W_down), _ptr(y), _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "moe_forward")
+
+
+def moe_forward_staged(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, events, stream=None):
+    """`events`: sequence of up to 6 hipEvent_t handles (ints) or None entries."""
+    n = len(events)
+    arr = (C.c_void_p * max(n, 1))(*[C.c_void_p(e) if e else None for e in events])
+    _check(lib().moe_forward_staged(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(W_gate), _ptr(W_up),
+                                    _ptr(W_down), _ptr(y), _ptr(workspace), _nbytes(workspace), _stream(stream),
+                                    arr, n), "moe_forward_staged")

@@ -1,0 +1,240 @@
+// C ABI of the library (include/moe.h): argument checks on the host, workspace layout, and
+// the stage launchers strung together.  Nothing here allocates, copies or synchronises.
+#include "moe_internal.hpp"
+
+namespace {
+
+using namespace moe;
+
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+moe_status check_config(const moe_config* c) {
+    if (c == nullptr) return MOE_ERR_NULL;
+    if (c->T < 0 || c->d < 1 || c->F < 1 || c->E < 1 || c->k < 1 || c->k > c->E) return MOE_ERR_SHAPE;
+    if (c->gating < MOE_GATE_SOFTMAX || c->gating > MOE_GATE_SIGMOID_NORM) return MOE_ERR_SHAPE;
+    if (c->reserved != 0) return MOE_ERR_SHAPE;
+    if (c->tile_m != 0 && c->tile_m != 32 && c->tile_m != 64 && c->tile_m != 128 && c->tile_m != 256)
+        return MOE_ERR_SHAPE;
+    if (c->E > kMaxExperts) return MOE_ERR_UNSUPPORTED;
+    if (c->d % 64 != 0 || c->F % 64 != 0) return MOE_ERR_UNSUPPORTED;
+    if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+size_t schedule_bytes(const moe_config* c, int M) {
+    return align_up((size_t)moe_max_blocks(c, M) * 2 * sizeof(int32_t)) + kAlign;   // + num_blocks
+}
+
+size_t hist_bytes(const moe_config* c) {
+    size_t n = (size_t)permute_chunks(*c) * c->E * sizeof(int32_t);
+    return align_up(n ? n : 1);
+}
+
+moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(moe_status s) {
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_NULL: return "required pointer is NULL";
+        case MOE_ERR_SHAPE: return "invalid shape or option";
+        case MOE_ERR_ALIGN: return "pointer is not 16-byte aligned";
+        case MOE_ERR_WORKSPACE: return "workspace too small";
+        case MOE_ERR_UNSUPPORTED: return "configuration outside the supported limits";
+        case MOE_ERR_HIP: return "HIP launch error";
+    }
+    return "unknown status";
+}
+
+int32_t moe_tile_m(const moe_config* c) {
+    if (check_config(c) != MOE_OK) return 0;
+    if (c->tile_m != 0) return c->tile_m;
+    const double mean = c->E > 0 ? (double)c->T * c->k / c->E : 0.0;
+    if (mean <= 32.0) return 32;
+    if (mean <= 64.0) return 64;
+    if (mean <= 192.0) return 128;
+    return 256;
+}
+
+int32_t moe_max_blocks(const moe_config* c, int32_t M) {
+    if (check_config(c) != MOE_OK || M < 1) return 0;
+    const long long R = (long long)c->T * c->k;
+    return (int32_t)(R / M + (R < c->E ? R : c->E));
+}
+
+size_t moe_permute_workspace_size(const moe_config* c) {
+    return check_config(c) == MOE_OK ? hist_bytes(c) : 0;
+}
+
+size_t moe_ffn_workspace_size(const moe_config* c) {
+    return check_config(c) == MOE_OK ? schedule_bytes(c, moe_tile_m(c)) : 0;
+}
+
+moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layout* out) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (out == nullptr) return MOE_ERR_NULL;
+    const size_t R = (size_t)c->T * c->k;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1); return o; };
+    out->topk_idx = take(R * sizeof(int32_t));
+    out->topk_w = take(R * sizeof(float));
+    out->counts = take((size_t)c->E * sizeof(int32_t));
+    out->offsets = take((size_t)(c->E + 1) * sizeof(int32_t));
+    out->row_of = take(R * sizeof(int32_t));
+    out->src_of = take(R * sizeof(int32_t));
+    out->x_perm = take(R * c->d * sizeof(uint16_t));
+    out->h = take(R * c->F * sizeof(uint16_t));
+    out->y_perm = take(R * c->d * sizeof(uint16_t));
+    out->scratch = take(hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
+    out->total = off;
+    return MOE_OK;
+}
+
+size_t moe_forward_workspace_size(const moe_config* c) {
+    moe_workspace_layout l;
+    return moe_forward_workspace_layout(c, &l) == MOE_OK ? l.total : 0;
+}
+
+moe_status moe_route(const moe_config* c, const void* x, const void* W_r, const float* bias,
+                     int32_t* topk_idx, float* topk_w, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!x || !W_r || !topk_idx || !topk_w) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(W_r)) return MOE_ERR_ALIGN;
+    if (c->T == 0) return MOE_OK;
+    return hip_status(launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w,
+                                   (hipStream_t)stream));
+}
+
+moe_status moe_permute(const moe_config* c, const void* x, const int32_t* topk_idx, int32_t* counts,
+                       int32_t* offsets, int32_t* row_of, int32_t* src_of, void* x_perm, void* workspace,
+                       size_t ws_bytes, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !counts || !offsets || !row_of || !src_of || !workspace) return MOE_ERR_NULL;
+    if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(x_perm) || misaligned(workspace)) return MOE_ERR_ALIGN;
+    if (ws_bytes < moe_permute_workspace_size(c)) return MOE_ERR_WORKSPACE;
+    if (c->T == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, (int32_t*)workspace, 0,
+                                        nullptr, nullptr, s);
+    if (e == hipSuccess && x != nullptr && c->T > 0)
+        e = launch_gather_rows(*c, (const uint16_t*)x, src_of, (uint16_t*)x_perm, s);
+    return hip_status(e);
+}
+
+moe_status moe_block_schedule(const moe_config* c, const int32_t* offsets, int32_t M, int32_t* blocks,
+                              int32_t* num_blocks, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (M < 1) return MOE_ERR_SHAPE;
+    if (!offsets || !blocks || !num_blocks) return MOE_ERR_NULL;
+    if (c->T == 0) return MOE_OK;
+    return hip_status(launch_block_schedule(*c, offsets, M, blocks, num_blocks, (hipStream_t)stream));
+}
+
+moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_t* offsets, const void* W_gate,
+                           const void* W_up, const void* W_down, void* h, void* y_perm, void* workspace,
+                           size_t ws_bytes, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!x_perm || !offsets || !W_gate || !W_up || !W_down || !h || !y_perm || !workspace) return MOE_ERR_NULL;
+    if (misaligned(x_perm) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) || misaligned(h) ||
+        misaligned(y_perm) || misaligned(workspace))
+        return MOE_ERR_ALIGN;
+    if (ws_bytes < moe_ffn_workspace_size(c)) return MOE_ERR_WORKSPACE;
+    if (c->T == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int M = moe_tile_m(c);
+    int32_t* blocks = (int32_t*)workspace;
+    int32_t* num_blocks = (int32_t*)((char*)workspace + schedule_bytes(c, M) - kAlign);
+    hipError_t e = launch_block_schedule(*c, offsets, M, blocks, num_blocks, s);
+    if (e == hipSuccess)
+        e = launch_gate_up(*c, M, (const uint16_t*)x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
+                           (const uint16_t*)W_up, (uint16_t*)h, s);
+    if (e == hipSuccess)
+        e = launch_down(*c, M, (const uint16_t*)h, offsets, blocks, num_blocks, (const uint16_t*)W_down,
+                        (uint16_t*)y_perm, s);
+    return hip_status(e);
+}
+
+moe_status moe_combine(const moe_config* c, const void* y_perm, const int32_t* row_of, const float* topk_w,
+                       void* y, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!y_perm || !row_of || !topk_w || !y) return MOE_ERR_NULL;
+    if (misaligned(y_perm) || misaligned(y)) return MOE_ERR_ALIGN;
+    if (c->T == 0) return MOE_OK;
+    return hip_status(launch_combine(*c, (const uint16_t*)y_perm, row_of, topk_w, (uint16_t*)y,
+                                     (hipStream_t)stream));
+}
+
+moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_r, const float* bias,
+                              const void* W_gate, const void* W_up, const void* W_down, void* y, void* workspace,
+                              size_t ws_bytes, void* stream, void* const* events, int32_t n_events) {
+    moe_workspace_layout l;
+    const moe_status st = moe_forward_workspace_layout(c, &l);
+    if (st != MOE_OK) return st;
+    if (!x || !W_r || !W_gate || !W_up || !W_down || !y || !workspace) return MOE_ERR_NULL;
+    if (n_events < 0 || (n_events > 0 && events == nullptr)) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(W_r) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) ||
+        misaligned(y) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
+        return MOE_ERR_ALIGN;
+    if (ws_bytes < l.total) return MOE_ERR_WORKSPACE;
+    if (c->T == 0) return MOE_OK;
+    hipStream_t s = (hipStream_t)stream;
+    char* ws = (char*)workspace;
+    int32_t* topk_idx = (int32_t*)(ws + l.topk_idx);
+    float* topk_w = (float*)(ws + l.topk_w);
+    int32_t* counts = (int32_t*)(ws + l.counts);
+    int32_t* offsets = (int32_t*)(ws + l.offsets);
+    int32_t* row_of = (int32_t*)(ws + l.row_of);
+    int32_t* src_of = (int32_t*)(ws + l.src_of);
+    uint16_t* x_perm = (uint16_t*)(ws + l.x_perm);
+    uint16_t* h = (uint16_t*)(ws + l.h);
+    uint16_t* y_perm = (uint16_t*)(ws + l.y_perm);
+    int32_t* hist = (int32_t*)(ws + l.scratch);
+    const int M = moe_tile_m(c);
+    int32_t* blocks = (int32_t*)(ws + l.scratch + hist_bytes(c));
+    int32_t* num_blocks = (int32_t*)((char*)blocks + schedule_bytes(c, M) - kAlign);
+
+    hipError_t e = hipSuccess;
+    auto mark = [&](int i) {
+        if (e == hipSuccess && i < n_events && events[i] != nullptr) e = hipEventRecord((hipEvent_t)events[i], s);
+    };
+    mark(0);
+    if (e == hipSuccess)
+        e = launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, s);
+    mark(1);
+    if (e == hipSuccess)
+        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);
+    if (e == hipSuccess) e = launch_gather_rows(*c, (const uint16_t*)x, src_of, x_perm, s);
+    mark(2);
+    if (e == hipSuccess)
+        e = launch_gate_up(*c, M, x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
+                           (const uint16_t*)W_up, h, s);
+    mark(3);
+    if (e == hipSuccess)
+        e = launch_down(*c, M, h, offsets, blocks, num_blocks, (const uint16_t*)W_down, y_perm, s);
+    mark(4);
+    if (e == hipSuccess) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);
+    mark(5);
+    return hip_status(e);
+}
+
+moe_status moe_forward(const moe_config* c, const void* x, const void* W_r, const float* bias, const void* W_gate,
+                       const void* W_up, const void* W_down, void* y, void* workspace, size_t ws_bytes,
+                       void* stream) {
+    return moe_forward_staged(c, x, W_r, bias, W_gate, W_up, W_down, y, workspace, ws_bytes, stream, nullptr, 0);
+}
+
+}  // extern "C"

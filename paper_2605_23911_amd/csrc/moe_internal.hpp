@@ -1,0 +1,63 @@
+// Internal declarations shared by the library's translation units (gfx950 only).
+// The public C ABI is include/moe.h; nothing here is exported.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe.h"
+
+namespace moe {
+
+constexpr int kMaxExperts = 256;      // one wavefront holds a logit row with <= 4 values per lane
+constexpr int kPermChunk = 1024;      // flat slots handled by one workgroup of the permutation kernels
+constexpr int kWave = 64;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// bf16 bit pattern -> float (exact).
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// float -> bf16, round to nearest even (v_cvt_pk_bf16_f32 on gfx950).
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
+    __bf16 h = (__bf16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+}
+
+// ---- launchers (each enqueues on `s` and returns hipGetLastError()) ----------------------
+hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
+                        int32_t* topk_idx, float* topk_w, hipStream_t s);
+
+// scratch: chunk histograms [nchunks, E] int32.  If blocks != nullptr the block schedule for
+// tile height M is emitted by the scan kernel as well.
+hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, int32_t* counts,
+                                int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
+                                int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s);
+hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int32_t* src_of,
+                              uint16_t* x_perm, hipStream_t s);
+hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M,
+                                 int32_t* blocks, int32_t* num_blocks, hipStream_t s);
+
+hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm, const int32_t* offsets,
+                          const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
+                          const uint16_t* wu, uint16_t* h, hipStream_t s);
+hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
+                       const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
+                       uint16_t* y_perm, hipStream_t s);
+
+hipError_t launch_combine(const moe_config& c, const uint16_t* y_perm, const int32_t* row_of,
+                          const float* topk_w, uint16_t* y, hipStream_t s);
+
+inline int permute_chunks(const moe_config& c) {
+    long long R = (long long)c.T * c.k;
+    return (int)((R + kPermChunk - 1) / kPermChunk);
+}
+
+}  // namespace moe

@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI: the library loads without a GPU, exports every symbol the
+header declares, sizes its workspaces sensibly and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2605_23911_amd as moe
+from paper_2605_23911_amd import binding
+from oracle import moe_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(moe.library_path()):
+        from paper_2605_23911_amd import build
+        build.build_library()
+    return moe.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "moe.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(moe_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_status_strings(L):
+    msgs = {L.moe_status_string(s).decode() for s in range(0, -7, -1)}
+    assert len(msgs) == 7 and "ok" in msgs
+
+
+def test_config_validation(L):
+    ok = moe.MoEConfig.of(64, 256, 512, 8, 2)
+    assert moe.tile_m(ok) == 32 and moe.forward_workspace_size(ok) > 0
+    bad = [moe.MoEConfig.of(-1, 256, 512, 8, 2), moe.MoEConfig.of(4, 256, 512, 8, 9),
+           moe.MoEConfig.of(4, 256, 512, 8, 0), moe.MoEConfig.of(4, 256, 512, 257, 2),
+           moe.MoEConfig.of(4, 250, 512, 8, 2), moe.MoEConfig.of(4, 256, 500, 8, 2),
+           moe.MoEConfig.of(4, 256, 512, 8, 2, gating=7), moe.MoEConfig.of(4, 256, 512, 8, 2, tile_m=48)]
+    for c in bad:
+        assert moe.tile_m(c) == 0 and moe.forward_workspace_size(c) == 0
+        assert moe.permute_workspace_size(c) == 0 and moe.ffn_workspace_size(c) == 0
+    st = L.moe_route(C.byref(bad[1]), 16, 16, None, 16, 16, None)
+    assert st == -2
+    assert L.moe_route(C.byref(bad[3]), 16, 16, None, 16, 16, None) == -5
+    assert L.moe_route(C.byref(bad[4]), 16, 16, None, 16, 16, None) == -5
+
+
+def test_null_alignment_and_workspace_errors_need_no_gpu(L):
+    c = moe.MoEConfig.of(64, 256, 512, 8, 2)
+    p = 4096   # never dereferenced: every call below must fail on the host
+    assert L.moe_route(C.byref(c), None, p, None, p, p, None) == -1
+    assert L.moe_route(C.byref(c), p + 2, p, None, p, p, None) == -3
+    assert L.moe_permute(C.byref(c), p, p, p, p, p, p, p, p, 0, None) == -4
+    assert L.moe_permute(C.byref(c), p, p, p, p, p, p, None, p, 1 << 20, None) == -1
+    assert L.moe_grouped_ffn(C.byref(c), p, p, p, p, p, p, p, p, 8, None) == -4
+    assert L.moe_grouped_ffn(C.byref(c), p, p, p, None, p, p, p, p, 1 << 20, None) == -1
+    assert L.moe_combine(C.byref(c), p, None, p, p, None) == -1
+    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, p, p, 16, None) == -4
+    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, p + 8, p, 1 << 30, None) == -3
+    assert L.moe_block_schedule(C.byref(c), p, 0, p, p, None) == -2
+    # T == 0 is a no-op that succeeds without a device
+    z = moe.MoEConfig.of(0, 256, 512, 8, 2)
+    assert L.moe_forward(C.byref(z), p, p, None, p, p, p, p, p, 1 << 20, None) == 0
+    assert L.moe_combine(C.byref(z), p, p, p, p, None) == 0
+
+
+def test_workspace_layout_is_ordered_and_sized(L):
+    for T, d, F, E, k in [(64, 256, 512, 8, 2), (512, 4096, 14336, 8, 2), (4096, 7168, 2048, 256, 8), (1, 64, 64, 1, 1)]:
+        c = moe.MoEConfig.of(T, d, F, E, k)
+        l = moe.forward_workspace_layout(c)
+        names = [n for n, _ in l._fields_][:-1]
+        offs = [getattr(l, n) for n in names]
+        assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+        R = T * k
+        assert l.h - l.x_perm >= R * d * 2 and l.y_perm - l.h >= R * F * 2
+        assert l.total == moe.forward_workspace_size(c) >= l.scratch + moe.ffn_workspace_size(c)
+        assert l.total < 2 * R * (2 * d + F) + (1 << 20) + 16 * R + 4 * E * (R // 1024 + 1) * 2
+
+
+def test_max_blocks_bounds_algorithm_1(L):
+    rng = np.random.default_rng(0)
+    for T, E, k in [(1, 8, 2), (64, 8, 2), (500, 64, 8), (3, 256, 8), (4096, 256, 8)]:
+        c = moe.MoEConfig.of(T, 256, 512, E, k)
+        for M in (32, 64, 128, 256):
+            ub = moe.max_blocks(c, M)
+            assert ub == (T * k) // M + min(E, T * k)
+            for _ in range(5):   # random and fully skewed splits of R rows over E experts
+                n = rng.multinomial(T * k, rng.dirichlet(np.full(E, 0.1)))
+                off = np.concatenate([[0], np.cumsum(n)])
+                assert len(orc.block_schedule(off, M)) <= ub
+
+
+def test_tile_height_choice(L):
+    assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 32      # 16 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 128    # 128 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2)) == 256   # 1024 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2, tile_m=64)) == 64
+
+
+def test_entry_points_refuse_cpu_tensors(L):
+    import torch
+    c = moe.MoEConfig.of(4, 64, 64, 2, 1)
+    t = torch.zeros(8, dtype=torch.int32)
+    with pytest.raises((ValueError, RuntimeError)):
+        moe.moe_combine(c, t, t, t, t)
