@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle's FFN is timed on (0 = auto)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
+                         "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -114,6 +117,14 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
     gate_up_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev_a, ev_b)]))
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device=dev)     # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.neg(src, out=dst)        # one elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- per-stage breakdown (outside the timed region)
     evs = [[new_event() for _ in range(6)] for _ in range(10)]
