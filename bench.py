@@ -40,6 +40,8 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle's FFN is timed on (0 = auto)")
+    ap.add_argument("--row-major", action="store_true",
+                    help="feed the GEMMs the row-major [E,N,K] weights instead of the one-time packed copy")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -90,6 +92,12 @@ def main():
     wd = torch.empty((s.E, s.d, s.F), dtype=torch.bfloat16, device=dev)
     mi.make_all_experts(s, args.seed, out=(wg, wu, wd))
     cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating, args.tile_m)
+    packed = None
+    if not args.row_major:      # model-load-time step, outside every timed region: same values, re-ordered
+        packed = torch.empty(moe.packed_weights_size(cfg), dtype=torch.uint8, device=dev)
+        moe.moe_pack_weights(cfg, wg, wu, wd, packed)
+        torch.cuda.synchronize()
+        wg = wu = wd = None
     lay = moe.forward_workspace_layout(cfg)
     ws = torch.zeros(lay.total, dtype=torch.uint8, device=dev)
     y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev)
@@ -101,7 +109,7 @@ def main():
         return ev
 
     for _ in range(args.warmup):
-        moe.moe_forward(cfg, x, wr, bias, wg, wu, wd, y, ws)
+        moe.moe_forward(cfg, x, wr, bias, wg, wu, wd, y, ws, W_packed=packed)
     torch.cuda.synchronize()
 
     # ---- timed region: K steps; events [2] and [3] bracket the gate+up kernel of every step
@@ -112,7 +120,7 @@ def main():
     t0 = time.perf_counter()
     for i in range(K):
         moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws,
-                               [None, None, ev_a[i].cuda_event, ev_b[i].cuda_event, None, None])
+                               [None, None, ev_a[i].cuda_event, ev_b[i].cuda_event, None, None], W_packed=packed)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -130,7 +138,7 @@ def main():
     evs = [[new_event() for _ in range(6)] for _ in range(10)]
     torch.cuda.synchronize()
     for row in evs:
-        moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws, [e.cuda_event for e in row])
+        moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws, [e.cuda_event for e in row], W_packed=packed)
     torch.cuda.synchronize()
     names = ["route", "permute", "gate_up", "down", "combine"]
     stages = {n: float(np.median([row[i].elapsed_time(row[i + 1]) for row in evs])) for i, n in enumerate(names)}
@@ -164,7 +172,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{s.name}-shaped MoE layer forward, T={s.T} tokens, d={s.d}, F={s.F}, E={s.E}, "
                                f"top-k={s.k}, gating={s.gating}, skew={args.skew}, seed={args.seed}",
-                   "tile_m": moe.tile_m(cfg)},
+                   "tile_m": moe.tile_m(cfg), "weights": "row-major" if args.row_major else "packed once at load"},
         "roofline": roofline,
         "layer": {"hbm_frac": layer_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                   "mfma_frac": layer_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,

@@ -78,7 +78,8 @@ typedef struct {
 const char* moe_status_string(moe_status s);
 
 /* Tile height (Alg. 1's M) the library uses for this config: cfg->tile_m if non-zero
- * (must be 32, 64, 128 or 256), else picked from the mean rows per expert T*k/E.
+ * (must be 32, 64, 96, 128, 160, 192 or 256), else the smallest of these that holds the mean
+ * rows per expert T*k/E plus four standard deviations of uniform routing (256 beyond that).
  * Returns 0 for an invalid config. */
 int32_t moe_tile_m(const moe_config* cfg);
 
@@ -118,14 +119,31 @@ moe_status moe_permute(const moe_config* cfg, const void* x, const int32_t* topk
 moe_status moe_block_schedule(const moe_config* cfg, const int32_t* offsets, int32_t M,
                               int32_t* blocks, int32_t* num_blocks, void* stream);
 
+/* Optional one-time weight packing (the weights of an inference layer are static).
+ * Sec. 3.2 stores each projection as a flattened E*N x K matrix; the GEMM kernels read it
+ * through per-lane 16-byte loads whose lanes touch 32 different rows.  moe_pack_weights
+ * re-orders the same bf16 values into the order those loads consume them, so that every load
+ * instruction reads 1 KiB contiguous and a wavefront streams one contiguous region:
+ *   unit = 16 bytes; order [expert][row block of 32][k step of 64][matrix][slot 0..3][lane 0..63];
+ *   unit (rb, kt, m, s, lane) = W_m[expert][32 rb + lane%32][64 kt + 16 s + 8 (lane/32) .. +8];
+ *   gate and up are interleaved (m = 0, 1) in the first 4*E*F*d bytes, the down projection
+ *   (m = 0 only) follows.
+ * `packed` must hold moe_packed_weights_size(cfg) bytes (= 6*E*d*F, the size of the three
+ * weight tensors), 256-byte aligned.  A packed buffer depends on d, F and E only, not on T, k. */
+size_t moe_packed_weights_size(const moe_config* cfg);
+moe_status moe_pack_weights(const moe_config* cfg, const void* W_gate, const void* W_up, const void* W_down,
+                            void* packed, void* stream);
+
 /* Stages 3+4, expert FFN as two block-scheduled grouped GEMMs (Sec. 3.2, 3.3, Eq. 4).
  *   x_perm [R,d] bf16 expert-contiguous, offsets [E+1]
  *   W_gate, W_up [E,F,d] bf16, W_down [E,d,F] bf16
+ *   W_packed: NULL, or moe_pack_weights' output for these weights; when it is given the kernels
+ *             read only the packed copy and W_gate, W_up, W_down may be NULL
  *   -> h [R,F] bf16 = SiLU(x W_gate^T) (.) (x W_up^T)  (fp32 accumulate, SiLU and product in
  *      fp32 registers, one rounding to bf16), y_perm [R,d] bf16 = h W_down^T (fp32 accumulate).
  * The block schedule is built on the device from `offsets`; no host synchronisation. */
 moe_status moe_grouped_ffn(const moe_config* cfg, const void* x_perm, const int32_t* offsets,
-                           const void* W_gate, const void* W_up, const void* W_down,
+                           const void* W_gate, const void* W_up, const void* W_down, const void* W_packed,
                            void* h, void* y_perm, void* workspace, size_t ws_bytes, void* stream);
 
 /* Stage 5, un-permute + weighted combine (Eq. 3, Sec. 3.5).
@@ -135,9 +153,9 @@ moe_status moe_combine(const moe_config* cfg, const void* y_perm, const int32_t*
                        const float* topk_w, void* y, void* stream);
 
 /* The whole layer: stages 1-5 enqueued back to back on `stream`, intermediates in
- * `workspace` at moe_forward_workspace_layout()'s offsets.  y [T,d] bf16. */
+ * `workspace` at moe_forward_workspace_layout()'s offsets.  y [T,d] bf16.  W_packed as above. */
 moe_status moe_forward(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
-                       const void* W_gate, const void* W_up, const void* W_down,
+                       const void* W_gate, const void* W_up, const void* W_down, const void* W_packed,
                        void* y, void* workspace, size_t ws_bytes, void* stream);
 
 /* moe_forward with timing hooks: `events` is an array of n_events hipEvent_t handles (as void*,
@@ -148,7 +166,7 @@ moe_status moe_forward(const moe_config* cfg, const void* x, const void* W_r, co
  * five stages; the per-stage breakdown mirrors the paper's Table 6). */
 #define MOE_NUM_STAGE_EVENTS 6
 moe_status moe_forward_staged(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
-                              const void* W_gate, const void* W_up, const void* W_down,
+                              const void* W_gate, const void* W_up, const void* W_down, const void* W_packed,
                               void* y, void* workspace, size_t ws_bytes, void* stream,
                               void* const* events, int32_t n_events);
 

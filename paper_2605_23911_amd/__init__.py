@@ -22,6 +22,8 @@ from .binding import (  # noqa: F401
     moe_forward,
     moe_forward_staged,
     moe_grouped_ffn,
+    moe_pack_weights,
+    packed_weights_size,
     moe_permute,
     moe_route,
     permute_workspace_size,

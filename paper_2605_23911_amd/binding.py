@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = (
     "moe_status_string", "moe_tile_m", "moe_permute_workspace_size", "moe_ffn_workspace_size",
     "moe_forward_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
-    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged",
+    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights",
 )
 
 
@@ -66,7 +66,8 @@ def lib() -> C.CDLL:
     L.moe_tile_m.argtypes = [cfgp]
     L.moe_max_blocks.restype = C.c_int32
     L.moe_max_blocks.argtypes = [cfgp, C.c_int32]
-    for n in ("moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size"):
+    for n in ("moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size",
+              "moe_packed_weights_size"):
         getattr(L, n).restype = C.c_size_t
         getattr(L, n).argtypes = [cfgp]
     L.moe_forward_workspace_layout.restype = C.c_int
@@ -78,13 +79,15 @@ def lib() -> C.CDLL:
     L.moe_block_schedule.restype = C.c_int
     L.moe_block_schedule.argtypes = [cfgp, i32p, C.c_int32, i32p, i32p, vp]
     L.moe_grouped_ffn.restype = C.c_int
-    L.moe_grouped_ffn.argtypes = [cfgp, vp, i32p, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.moe_grouped_ffn.argtypes = [cfgp, vp, i32p, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.moe_pack_weights.restype = C.c_int
+    L.moe_pack_weights.argtypes = [cfgp, vp, vp, vp, vp, vp]
     L.moe_combine.restype = C.c_int
     L.moe_combine.argtypes = [cfgp, vp, i32p, f32p, vp, vp]
     L.moe_forward.restype = C.c_int
-    L.moe_forward.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, C.c_size_t, vp]
+    L.moe_forward.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
     L.moe_forward_staged.restype = C.c_int
-    L.moe_forward_staged.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(C.c_void_p),
+    L.moe_forward_staged.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(C.c_void_p),
                                      C.c_int32]
     _lib = L
     return L
@@ -154,10 +157,19 @@ def moe_block_schedule(cfg, offsets, M, blocks, num_blocks, stream=None):
                                     _stream(stream)), "moe_block_schedule")
 
 
-def moe_grouped_ffn(cfg, x_perm, offsets, W_gate, W_up, W_down, h, y_perm, workspace, stream=None):
+def packed_weights_size(cfg) -> int:
+    return lib().moe_packed_weights_size(C.byref(cfg))
+
+
+def moe_pack_weights(cfg, W_gate, W_up, W_down, packed, stream=None):
+    _check(lib().moe_pack_weights(C.byref(cfg), _ptr(W_gate), _ptr(W_up), _ptr(W_down), _ptr(packed),
+                                  _stream(stream)), "moe_pack_weights")
+
+
+def moe_grouped_ffn(cfg, x_perm, offsets, W_gate, W_up, W_down, h, y_perm, workspace, W_packed=None, stream=None):
     _check(lib().moe_grouped_ffn(C.byref(cfg), _ptr(x_perm), _ptr(offsets), _ptr(W_gate), _ptr(W_up),
-                                 _ptr(W_down), _ptr(h), _ptr(y_perm), _ptr(workspace), _nbytes(workspace),
-                                 _stream(stream)), "moe_grouped_ffn")
+                                 _ptr(W_down), _ptr(W_packed), _ptr(h), _ptr(y_perm), _ptr(workspace),
+                                 _nbytes(workspace), _stream(stream)), "moe_grouped_ffn")
 
 
 def moe_combine(cfg, y_perm, row_of, topk_w, y, stream=None):
@@ -165,16 +177,16 @@ def moe_combine(cfg, y_perm, row_of, topk_w, y, stream=None):
            "moe_combine")
 
 
-def moe_forward(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, stream=None):
+def moe_forward(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, W_packed=None, stream=None):
     _check(lib().moe_forward(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(W_gate), _ptr(W_up),
-                             _ptr(W_down), _ptr(y), _ptr(workspace), _nbytes(workspace), _stream(stream)),
-           "moe_forward")
+                             _ptr(W_down), _ptr(W_packed), _ptr(y), _ptr(workspace), _nbytes(workspace),
+                             _stream(stream)), "moe_forward")
 
 
-def moe_forward_staged(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, events, stream=None):
+def moe_forward_staged(cfg, x, W_r, bias, W_gate, W_up, W_down, y, workspace, events, W_packed=None, stream=None):
     """`events`: sequence of up to 6 hipEvent_t handles (ints) or None entries."""
     n = len(events)
     arr = (C.c_void_p * max(n, 1))(*[C.c_void_p(e) if e else None for e in events])
     _check(lib().moe_forward_staged(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(W_gate), _ptr(W_up),
-                                    _ptr(W_down), _ptr(y), _ptr(workspace), _nbytes(workspace), _stream(stream),
-                                    arr, n), "moe_forward_staged")
+                                    _ptr(W_down), _ptr(W_packed), _ptr(y), _ptr(workspace), _nbytes(workspace),
+                                    _stream(stream), arr, n), "moe_forward_staged")

@@ -1,5 +1,7 @@
 // C ABI of the library (include/moe.h): argument checks on the host, workspace layout, and
 // the stage launchers strung together.  Nothing here allocates, copies or synchronises.
+#include <cmath>
+
 #include "moe_internal.hpp"
 
 namespace {
@@ -10,13 +12,20 @@ constexpr size_t kAlign = 256;
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+constexpr int kTileHeights[] = {32, 64, 96, 128, 160, 192, 256};
+
+bool valid_tile_m(int m) {
+    for (int v : kTileHeights)
+        if (v == m) return true;
+    return false;
+}
+
 moe_status check_config(const moe_config* c) {
     if (c == nullptr) return MOE_ERR_NULL;
     if (c->T < 0 || c->d < 1 || c->F < 1 || c->E < 1 || c->k < 1 || c->k > c->E) return MOE_ERR_SHAPE;
     if (c->gating < MOE_GATE_SOFTMAX || c->gating > MOE_GATE_SIGMOID_NORM) return MOE_ERR_SHAPE;
     if (c->reserved != 0) return MOE_ERR_SHAPE;
-    if (c->tile_m != 0 && c->tile_m != 32 && c->tile_m != 64 && c->tile_m != 128 && c->tile_m != 256)
-        return MOE_ERR_SHAPE;
+    if (c->tile_m != 0 && !valid_tile_m(c->tile_m)) return MOE_ERR_SHAPE;
     if (c->E > kMaxExperts) return MOE_ERR_UNSUPPORTED;
     if (c->d % 64 != 0 || c->F % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
@@ -56,10 +65,13 @@ const char* moe_status_string(moe_status s) {
 int32_t moe_tile_m(const moe_config* c) {
     if (check_config(c) != MOE_OK) return 0;
     if (c->tile_m != 0) return c->tile_m;
-    const double mean = c->E > 0 ? (double)c->T * c->k / c->E : 0.0;
-    if (mean <= 32.0) return 32;
-    if (mean <= 64.0) return 64;
-    if (mean <= 192.0) return 128;
+    // Rows per expert under near-uniform routing are Binomial(T, k/E): take the smallest tile
+    // that holds mean + 4 sigma, so that (almost) every expert is ONE tile and its weights are
+    // streamed once.  Beyond 192 rows the 256-row tile skips its empty 64-row groups itself.
+    const double p = (double)c->k / c->E;
+    const double need = c->T * p + 4.0 * sqrt(c->T * p * (1.0 - p));
+    for (int v : kTileHeights)
+        if (need <= v && v < 256) return v;
     return 256;
 }
 
@@ -142,14 +154,31 @@ moe_status moe_block_schedule(const moe_config* c, const int32_t* offsets, int32
     return hip_status(launch_block_schedule(*c, offsets, M, blocks, num_blocks, (hipStream_t)stream));
 }
 
-moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_t* offsets, const void* W_gate,
-                           const void* W_up, const void* W_down, void* h, void* y_perm, void* workspace,
-                           size_t ws_bytes, void* stream) {
+size_t moe_packed_weights_size(const moe_config* c) {
+    return check_config(c) == MOE_OK ? packed_gate_up_bytes(*c) + packed_down_bytes(*c) : 0;
+}
+
+moe_status moe_pack_weights(const moe_config* c, const void* W_gate, const void* W_up, const void* W_down,
+                            void* packed, void* stream) {
     const moe_status st = check_config(c);
     if (st != MOE_OK) return st;
-    if (!x_perm || !offsets || !W_gate || !W_up || !W_down || !h || !y_perm || !workspace) return MOE_ERR_NULL;
+    if (!W_gate || !W_up || !W_down || !packed) return MOE_ERR_NULL;
+    if (misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) ||
+        (reinterpret_cast<uintptr_t>(packed) & (kAlign - 1)) != 0)
+        return MOE_ERR_ALIGN;
+    return hip_status(launch_pack(*c, (const uint16_t*)W_gate, (const uint16_t*)W_up, (const uint16_t*)W_down,
+                                  (uint16_t*)packed, (hipStream_t)stream));
+}
+
+moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_t* offsets, const void* W_gate,
+                           const void* W_up, const void* W_down, const void* W_packed, void* h, void* y_perm,
+                           void* workspace, size_t ws_bytes, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!x_perm || !offsets || !h || !y_perm || !workspace) return MOE_ERR_NULL;
+    if (!W_packed && (!W_gate || !W_up || !W_down)) return MOE_ERR_NULL;
     if (misaligned(x_perm) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) || misaligned(h) ||
-        misaligned(y_perm) || misaligned(workspace))
+        misaligned(y_perm) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(W_packed) & (kAlign - 1)) != 0)
         return MOE_ERR_ALIGN;
     if (ws_bytes < moe_ffn_workspace_size(c)) return MOE_ERR_WORKSPACE;
     if (c->T == 0) return MOE_OK;
@@ -157,12 +186,14 @@ moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_
     const int M = moe_tile_m(c);
     int32_t* blocks = (int32_t*)workspace;
     int32_t* num_blocks = (int32_t*)((char*)workspace + schedule_bytes(c, M) - kAlign);
+    const uint16_t* pgu = (const uint16_t*)W_packed;
+    const uint16_t* pdn = pgu ? pgu + packed_gate_up_bytes(*c) / sizeof(uint16_t) : nullptr;
     hipError_t e = launch_block_schedule(*c, offsets, M, blocks, num_blocks, s);
     if (e == hipSuccess)
         e = launch_gate_up(*c, M, (const uint16_t*)x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
-                           (const uint16_t*)W_up, (uint16_t*)h, s);
+                           (const uint16_t*)W_up, pgu, (uint16_t*)h, s);
     if (e == hipSuccess)
-        e = launch_down(*c, M, (const uint16_t*)h, offsets, blocks, num_blocks, (const uint16_t*)W_down,
+        e = launch_down(*c, M, (const uint16_t*)h, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn,
                         (uint16_t*)y_perm, s);
     return hip_status(e);
 }
@@ -179,20 +210,25 @@ moe_status moe_combine(const moe_config* c, const void* y_perm, const int32_t* r
 }
 
 moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_r, const float* bias,
-                              const void* W_gate, const void* W_up, const void* W_down, void* y, void* workspace,
-                              size_t ws_bytes, void* stream, void* const* events, int32_t n_events) {
+                              const void* W_gate, const void* W_up, const void* W_down, const void* W_packed,
+                              void* y, void* workspace, size_t ws_bytes, void* stream, void* const* events,
+                              int32_t n_events) {
     moe_workspace_layout l;
     const moe_status st = moe_forward_workspace_layout(c, &l);
     if (st != MOE_OK) return st;
-    if (!x || !W_r || !W_gate || !W_up || !W_down || !y || !workspace) return MOE_ERR_NULL;
+    if (!x || !W_r || !y || !workspace) return MOE_ERR_NULL;
+    if (!W_packed && (!W_gate || !W_up || !W_down)) return MOE_ERR_NULL;
     if (n_events < 0 || (n_events > 0 && events == nullptr)) return MOE_ERR_NULL;
     if (misaligned(x) || misaligned(W_r) || misaligned(W_gate) || misaligned(W_up) || misaligned(W_down) ||
-        misaligned(y) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0)
+        misaligned(y) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
+        (reinterpret_cast<uintptr_t>(W_packed) & (kAlign - 1)) != 0)
         return MOE_ERR_ALIGN;
     if (ws_bytes < l.total) return MOE_ERR_WORKSPACE;
     if (c->T == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
+    const uint16_t* pgu = (const uint16_t*)W_packed;
+    const uint16_t* pdn = pgu ? pgu + packed_gate_up_bytes(*c) / sizeof(uint16_t) : nullptr;
     int32_t* topk_idx = (int32_t*)(ws + l.topk_idx);
     float* topk_w = (float*)(ws + l.topk_w);
     int32_t* counts = (int32_t*)(ws + l.counts);
@@ -221,10 +257,10 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     mark(2);
     if (e == hipSuccess)
         e = launch_gate_up(*c, M, x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
-                           (const uint16_t*)W_up, h, s);
+                           (const uint16_t*)W_up, pgu, h, s);
     mark(3);
     if (e == hipSuccess)
-        e = launch_down(*c, M, h, offsets, blocks, num_blocks, (const uint16_t*)W_down, y_perm, s);
+        e = launch_down(*c, M, h, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm, s);
     mark(4);
     if (e == hipSuccess) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);
     mark(5);
@@ -232,9 +268,10 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
 }
 
 moe_status moe_forward(const moe_config* c, const void* x, const void* W_r, const float* bias, const void* W_gate,
-                       const void* W_up, const void* W_down, void* y, void* workspace, size_t ws_bytes,
-                       void* stream) {
-    return moe_forward_staged(c, x, W_r, bias, W_gate, W_up, W_down, y, workspace, ws_bytes, stream, nullptr, 0);
+                       const void* W_up, const void* W_down, const void* W_packed, void* y, void* workspace,
+                       size_t ws_bytes, void* stream) {
+    return moe_forward_staged(c, x, W_r, bias, W_gate, W_up, W_down, W_packed, y, workspace, ws_bytes, stream,
+                              nullptr, 0);
 }
 
 }  // extern "C"

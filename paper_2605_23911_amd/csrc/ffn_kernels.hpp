@@ -1,0 +1,445 @@
+// Block-scheduled grouped GEMMs of the expert FFN on bf16 MFMA (gfx950).
+// Paper: Sec. 3.2 (one launch, workgroup -> (expert, row offset) through the block schedule,
+// partial tiles masked), Sec. 3.3 (gate and up projections from one shared input tile, two
+// accumulators, SiLU(gate)*up in fp32 registers, a single 2-byte intermediate), Eq. 4.
+//
+// What differs from the paper's A100 design: the MFMA computes the TRANSPOSED tile
+//     C^T[f, row] = sum_k W[f, k] * X[row, k]
+// with the weight rows as the first MFMA operand.  The stored weight layout ([out, in], the
+// reduction dim contiguous) is then exactly the per-lane operand layout, so weights go
+// HBM -> VGPR with 16-byte loads and never touch LDS.  The MFMA sums over k, so which k a
+// fragment slot carries is free as long as both operands agree: MFMA s of a 64-wide step takes
+// k = 16 s + 8 (lane / 32) + 0..7, which makes the two lanes of a weight row read 32 contiguous
+// bytes per load instruction (one 64-byte L1 access instead of two).  Each wavefront owns its own weight rows
+// and all token rows of the tile, so every weight byte is fetched once per workgroup.  In C^T
+// a lane holds four consecutive output features of one token row (8-byte packed bf16 stores).
+//
+// PACKED weights: lanes of one load instruction read 32 different weight rows, 16 bytes each,
+// which costs one L1 access per lane.  moe_pack_weights re-orders the weights once (weights are
+// static at inference) into the order the loads consume them, [expert][32-row block][64-k step]
+// [matrix][s][lane] x 16 bytes, so that one load instruction reads 1 KiB contiguous and a
+// wavefront streams one contiguous region.  Both layouts are supported by every kernel.
+//
+// Two kernel families share that mapping:
+//   tile_kernel    token tile (32*JB rows) staged in LDS and shared by the four wavefronts;
+//                  for tiles of 64..256 rows (HBM-bound with real MFMA load, or MFMA-bound).
+//   skinny_kernel  <= 64 token rows, token fragments loaded straight from L2 by each
+//                  wavefront: no LDS, no barrier in the reduction loop; optionally the four
+//                  wavefronts split K (down projection of few-expert models, where there are
+//                  too few output rows to fill 256 CUs otherwise).
+#pragma once
+
+#include <cstdlib>
+#include <type_traits>
+#include <utility>
+
+#include "moe_internal.hpp"
+
+namespace moe {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBK = 64;            // reduction elements per pipeline step
+constexpr int kLdsStride = 72;     // bf16 elements per staged token row: 64 + 8 pad (144 B)
+
+struct GemmArgs {
+    const uint16_t* X;          // [R, K] expert-contiguous rows
+    const uint16_t* W0;         // [E, N, K]  gate (or down)
+    const uint16_t* W1;         // [E, N, K]  up   (unused for down)
+    const uint16_t* P;          // packed weights of this projection (PACKED kernels), else unused
+    uint16_t* Out;              // [R, N]
+    const int32_t* offsets;     // [E+1]
+    const int32_t* blocks;      // [*, 2] (expert, row offset inside the expert)
+    const int32_t* num_blocks;  // device scalar
+    int R, N, K, n_tiles_n;
+};
+
+template <int... Is, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+// Calls f(integral_constant<0>) ... f(integral_constant<N-1>): indices are compile-time
+// constants in the source, so register arrays never need a loop-unrolling pass to be promoted.
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) {
+    // SiLU(g) * u with SiLU(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives -0.
+    return g * __frcp_rn(1.0f + __expf(-g)) * u;
+}
+
+// Weight fragment addressing.  Unpacked: row-major rows, element (row, k).  Packed: 16-byte
+// units ordered [expert][row block][k step][matrix][s][lane].
+template <bool PACKED, int NM>
+struct WAddr {
+    static constexpr int kStep = PACKED ? NM * 4 * 512 : kBK;   // elements per 64-wide k step
+    static constexpr int sStep = PACKED ? 512 : 16;              // elements per MFMA slot s
+    __device__ static __forceinline__ const uint16_t* base(const GemmArgs& a, int e, int row_block, int m, int lane) {
+        const int li = lane & 31, half = lane >> 5;
+        const int nrb = a.N / 32;
+        if constexpr (PACKED) {
+            const int rb = row_block < nrb ? row_block : nrb - 1;   // ragged last feature tile
+            return a.P + ((size_t)e * nrb + rb) * (size_t)(a.K / kBK) * kStep + m * 4 * 512 + lane * 8;
+        } else {
+            int row = row_block * 32 + li;
+            row = row < a.N ? row : a.N - 1;
+            return (m == 0 ? a.W0 : a.W1) + ((size_t)e * a.N + row) * a.K + half * 8;
+        }
+    }
+};
+
+// Block schedule entry -> tile geometry (Alg. 1: block = (expert, row offset)).
+struct Tile {
+    int e, row0, rows;
+};
+__device__ __forceinline__ bool load_tile(const GemmArgs& a, int tile, int BM, Tile& t) {
+    if (tile >= *a.num_blocks) return false;
+    t.e = a.blocks[2 * tile];
+    const int r_in = a.blocks[2 * tile + 1];
+    const int seg0 = a.offsets[t.e];
+    const int n_e = a.offsets[t.e + 1] - seg0;
+    t.row0 = seg0 + r_in;
+    t.rows = (n_e - r_in) < BM ? (n_e - r_in) : BM;
+    return true;
+}
+
+// Workgroup -> (tile, feature tile): tile-major, feature tiles of one block-schedule entry
+// adjacent.  The hardware deals workgroups to the 8 XCDs round-robin; with a feature-tile count
+// that is a multiple of 8 the row tiles of one expert that share a weight panel land on the
+// same XCD (and run at about the same time), so the panel is fetched into one L2 only.
+// (Measured: cutting the work into 8 contiguous per-XCD chunks instead is slower at large T
+// because it separates exactly those row tiles in time.)
+__device__ __forceinline__ bool map_workgroup(const GemmArgs& a, int& tile, int& nt) {
+    tile = blockIdx.x / a.n_tiles_n;
+    nt = blockIdx.x - tile * a.n_tiles_n;
+    return true;
+}
+
+// Epilogue for one 32x32 MFMA block: the lane holds, for token row (j*32 + lane%32), the
+// features q*8 + 4*(lane/32) + 0..3 (q = 0..3) of the block that starts at feature f0.
+template <bool GATEUP>
+__device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, uint16_t* out_row, int f0, int half,
+                                            int N) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const int f = f0 + q * 8 + half * 4;
+        if (f < N) {
+            float o[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) o[v] = GATEUP ? silu_mul(g[q * 4 + v], u[q * 4 + v]) : g[q * 4 + v];
+            uint2 pk;
+            pk.x = pack2_bf16(o[0], o[1]);
+            pk.y = pack2_bf16(o[2], o[3]);
+            *reinterpret_cast<uint2*>(out_row + f) = pk;
+        }
+    }
+}
+
+// =============================================================================================
+// tile_kernel: JB*32 token rows in LDS, IB 32-row weight blocks per wavefront and matrix.
+// =============================================================================================
+template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED>
+__device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
+    constexpr int NM = GATEUP ? 2 : 1;
+    constexpr int NI = IB * NM;
+    constexpr int BM = JB * 32;
+    constexpr int BN = 4 * IB * 32;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int li = lane & 31, half = lane >> 5;
+    const int K = a.K, N = a.N;
+    const int KT = K / kBK;
+    const int n0w = nt * BN + wave * (IB * 32);
+
+    typedef WAddr<PACKED, NM> WA;
+    const uint16_t* wp[NI];   // out-of-range rows of a ragged last feature tile are clamped, stores masked
+    static_for<NM>([&](auto m) {
+        static_for<IB>([&](auto ib) { wp[m * IB + ib] = WA::base(a, t.e, n0w / 32 + ib, m, lane); });
+    });
+    // token tile: thread -> (row tid/8 + 32p, 16-byte chunk tid%8); rows clamped inside X
+    const uint16_t* xp[JBE];
+    static_for<JBE>([&](auto p) {
+        int row = t.row0 + (tid >> 3) + 32 * p;
+        row = row < a.R ? row : a.R - 1;
+        xp[p] = a.X + (size_t)row * K + (tid & 7) * 8;
+    });
+    const int xs_store = (tid >> 3) * kLdsStride + (tid & 7) * 8;
+    const int xs_read = li * kLdsStride + half * 8;
+
+    f32x16 acc[NI][JBE];
+    static_for<NI>([&](auto i) {
+        static_for<JBE>([&](auto j) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        });
+    });
+
+    uint4 wreg[STAGES][NI][4];
+    typedef uint32_t xreg_t __attribute__((ext_vector_type(4 * JBE)));
+    xreg_t xreg[XD];   // each set is one SSA vector value (a plain array is not reliably kept in registers)
+
+    // Software pipeline.  In step kt the wavefront issues, in this order, the token-tile loads
+    // of step kt+XD and the weight loads of step kt+STAGES-1, runs the MFMAs of step kt from
+    // LDS buffer kt%2 and its weight registers, then writes the token tile of step kt+1 (loaded
+    // XD-1 steps ago) into the other LDS buffer.  Loads complete in issue order, so that last
+    // wait leaves everything issued later in flight.  All loads are unconditional (the step
+    // index is clamped to the last step, which is re-read harmlessly): straight-line code.
+    auto load_w = [&](int kt, auto st) {
+        const int kc = kt < KT ? kt : KT - 1;
+        static_for<NI>([&](auto i) {
+            static_for<4>([&](auto s) {
+                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+            });
+        });
+    };
+    auto load_x = [&](int kt, auto xs_) {
+        const int kc = kt < KT ? kt : KT - 1;
+        static_for<JBE>([&](auto p) {
+            const uint4 v = *reinterpret_cast<const uint4*>(xp[p] + (size_t)kc * kBK);
+            xreg[xs_][4 * p + 0] = v.x;
+            xreg[xs_][4 * p + 1] = v.y;
+            xreg[xs_][4 * p + 2] = v.z;
+            xreg[xs_][4 * p + 3] = v.w;
+        });
+    };
+    auto store_x = [&](int buf, auto xs_) {
+        static_for<JBE>([&](auto p) {
+            *reinterpret_cast<uint4*>(&xs[buf * BM * kLdsStride + xs_store + p * 32 * kLdsStride]) =
+                make_uint4(xreg[xs_][4 * p + 0], xreg[xs_][4 * p + 1], xreg[xs_][4 * p + 2], xreg[xs_][4 * p + 3]);
+        });
+    };
+    // `u` = kt modulo the unroll factor UNR (a multiple of both STAGES and XD), compile-time
+    auto step = [&](int kt, auto u) {
+        const int buf = kt & 1;
+        load_x(kt + XD, std::integral_constant<int, (u + XD) % XD>{});           // set (kt+XD)%XD == kt%XD
+        load_w(kt + STAGES - 1, std::integral_constant<int, (u + STAGES - 1) % STAGES>{});
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4>([&](auto s) {
+            bf16x8 xf[JBE];
+            static_for<JBE>([&](auto j) {
+                xf[j] = *reinterpret_cast<const bf16x8*>(
+                    &xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride + s * 16]);
+            });
+            static_for<NI>([&](auto i) {
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
+                static_for<JBE>([&](auto j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[j], acc[i][j], 0, 0, 0);
+                });
+            });
+        });
+        __builtin_amdgcn_sched_barrier(0);
+        store_x(buf ^ 1, std::integral_constant<int, (u + 1) % XD>{});            // token tile of step kt+1
+        __syncthreads();
+    };
+    // NOTE on register sets: in step kt the set kt%XD is free (its tile, step kt, went to LDS at
+    // the end of step kt-1), so the loads of step kt+XD reuse it; with XD == 1 the single set is
+    // loaded at the top of the step and stored at its end.
+
+    static_for<STAGES - 1>([&](auto st) { load_w(st, st); });
+    load_x(0, std::integral_constant<int, 0>{});
+    store_x(0, std::integral_constant<int, 0>{});
+    static_for<XD - 1>([&](auto q) { load_x(q + 1, std::integral_constant<int, (q + 1) % XD>{}); });
+    __syncthreads();
+
+    constexpr int UNR = (STAGES % XD == 0) ? STAGES : STAGES * XD;
+    int kt = 0;
+    for (; kt + UNR <= KT; kt += UNR) static_for<UNR>([&](auto u) { step(kt + u, u); });
+    static_for<UNR>([&](auto u) {
+        if (kt + u < KT) step(kt + u, u);
+    });
+
+    static_for<IB>([&](auto ib) {
+        static_for<JBE>([&](auto j) {
+            const int tr = j * 32 + li;
+            if (tr < t.rows)
+                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * N,
+                                    n0w + ib * 32, half, N);
+        });
+    });
+}
+
+// DYN: pick the body for the number of 64-row groups the tile really holds (ragged last tile
+// of an expert), so that empty column blocks cost neither LDS traffic nor MFMA issue slots.
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED>
+__global__ __launch_bounds__(kThreads) void tile_kernel(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
+    Tile t;
+    int tile, nt;
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, JB * 32, t)) return;
+    if constexpr (DYN && JB == 8) {
+        const int jbe = (t.rows + 31) / 32;
+        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+    }
+    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+}
+
+// =============================================================================================
+// skinny_kernel: JB*32 <= 64 token rows, fragments straight from global memory, no LDS in the
+// reduction loop.  SPLITK == 1: the four wavefronts own four different 32-row weight blocks.
+// SPLITK == 4: they share one weight block and each reduces a quarter of K; partial sums are
+// added in wavefront order through LDS (fixed order: bit-reproducible).
+// =============================================================================================
+template <int JB, bool GATEUP, int STAGES, int SPLITK, bool PACKED>
+__global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
+    constexpr int NM = GATEUP ? 2 : 1;
+    constexpr int BM = JB * 32;
+    constexpr int BN = (SPLITK == 1) ? 128 : 32;
+    __shared__ float red[(SPLITK == 1) ? 1 : 3 * NM * JB * 16 * kWave];
+
+    Tile t;
+    int tile, nt;
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, BM, t)) return;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int li = lane & 31, half = lane >> 5;
+    const int K = a.K, N = a.N;
+    const int KT = K / kBK;
+    const int n0w = nt * BN + (SPLITK == 1 ? wave * 32 : 0);
+    const int per = (KT + SPLITK - 1) / SPLITK;
+    const int kt_begin = (SPLITK == 1) ? 0 : wave * per;
+    // last step of this wavefront's K range; below kt_begin when the range is empty
+    const int kt_last = ((SPLITK == 1) ? KT : ((kt_begin + per) < KT ? (kt_begin + per) : KT)) - 1;
+
+    typedef WAddr<PACKED, NM> WA;
+    const uint16_t* wp[NM];
+    static_for<NM>([&](auto m) { wp[m] = WA::base(a, t.e, n0w / 32, m, lane); });
+    const uint16_t* xp[JB];
+    static_for<JB>([&](auto j) {
+        int row = t.row0 + j * 32 + li;
+        row = row < a.R ? row : a.R - 1;
+        xp[j] = a.X + (size_t)row * K + half * 8;
+    });
+
+    f32x16 acc[NM][JB];
+    static_for<NM>([&](auto i) {
+        static_for<JB>([&](auto j) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        });
+    });
+
+    uint4 wreg[STAGES][NM][4];
+    uint4 xreg[STAGES][JB][4];
+    auto load = [&](int kt, auto st) {
+        int kc = kt < kt_last ? kt : kt_last;   // clamped into [0, KT): always in bounds
+        kc = kc > 0 ? kc : 0;
+        static_for<NM>([&](auto i) {
+            static_for<4>([&](auto s) {
+                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+            });
+        });
+        static_for<JB>([&](auto j) {
+            static_for<4>([&](auto s) {
+                xreg[st][j][s] = *reinterpret_cast<const uint4*>(xp[j] + (size_t)kc * kBK + s * 16);
+            });
+        });
+    };
+    auto step = [&](int kt, auto st) {
+        load(kt + STAGES - 1, std::integral_constant<int, (st + STAGES - 1) % STAGES>{});
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4>([&](auto s) {
+            static_for<NM>([&](auto i) {
+                static_for<JB>([&](auto j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(bf16x8, wreg[st][i][s]), __builtin_bit_cast(bf16x8, xreg[st][j][s]),
+                        acc[i][j], 0, 0, 0);
+                });
+            });
+        });
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    static_for<STAGES - 1>([&](auto st) { load(kt_begin + st, st); });
+    int kt = kt_begin;
+    for (; kt + STAGES - 1 <= kt_last; kt += STAGES) static_for<STAGES>([&](auto st) { step(kt + st, st); });
+    static_for<STAGES>([&](auto st) {
+        if (kt + st <= kt_last) step(kt + st, st);
+    });
+
+    if constexpr (SPLITK > 1) {
+        // wavefronts 1..3 park their partial sums; wavefront 0 adds them in order 1, 2, 3
+        constexpr int PER_WAVE = NM * JB * 16 * kWave;
+        if (wave > 0) {
+            static_for<NM>([&](auto i) {
+                static_for<JB>([&](auto j) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        red[(wave - 1) * PER_WAVE + ((i * JB + j) * 16 + v) * kWave + lane] = acc[i][j][v];
+                });
+            });
+        }
+        __syncthreads();
+        if (wave > 0) return;
+        for (int w = 0; w < SPLITK - 1; ++w) {
+            static_for<NM>([&](auto i) {
+                static_for<JB>([&](auto j) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[i][j][v] += red[w * PER_WAVE + ((i * JB + j) * 16 + v) * kWave + lane];
+                });
+            });
+        }
+    }
+    static_for<JB>([&](auto j) {
+        const int tr = j * 32 + li;
+        if (tr < t.rows)
+            store_block<GATEUP>(acc[0][j], acc[GATEUP ? 1 : 0][j], a.Out + (size_t)(t.row0 + tr) * N, n0w, half, N);
+    });
+}
+
+// =============================================================================================
+// launch helpers
+// =============================================================================================
+typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
+
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED>
+hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
+    constexpr int BN = 4 * IB * 32;
+    constexpr size_t lds = (size_t)2 * JB * 32 * kLdsStride * sizeof(uint16_t);
+    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED>;
+    static bool attr_done = false;   // dynamic LDS above 64 KB needs an explicit opt-in, once per process
+    if (!attr_done && lds > 65536) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    GemmArgs args = a;
+    args.n_tiles_n = (a.N + BN - 1) / BN;
+    const long long grid = (long long)max_blocks * args.n_tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
+    return hipGetLastError();
+}
+
+template <int JB, bool GATEUP, int STAGES, int SPLITK, bool PACKED>
+hipError_t launch_skinny(const GemmArgs& a, int max_blocks, hipStream_t s) {
+    constexpr int BN = (SPLITK == 1) ? 128 : 32;
+    GemmArgs args = a;
+    args.n_tiles_n = (a.N + BN - 1) / BN;
+    const long long grid = (long long)max_blocks * args.n_tiles_n;
+    hipLaunchKernelGGL((skinny_kernel<JB, GATEUP, STAGES, SPLITK, PACKED>), dim3((unsigned)grid), dim3(kThreads), 0,
+                       s, args);
+    return hipGetLastError();
+}
+
+struct Variant {
+    int M;          // tile height (Alg. 1's M) this variant implements
+    bool packed;    // consumes moe_pack_weights' layout
+    launch_fn fn;
+};
+
+// A tuning run may force a variant by table index through an environment variable; the index
+// is ignored unless that variant matches the tile height and weight layout in use.
+inline int env_variant(const char* name, int count, int M, bool packed, const Variant* table) {
+    const char* v = std::getenv(name);
+    if (v == nullptr) return -1;
+    const int id = std::atoi(v);
+    return (id >= 0 && id < count && table[id].M == M && table[id].packed == packed) ? id : -1;
+}
+
+}  // namespace
+
+}  // namespace moe

@@ -45,12 +45,19 @@ hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int3
 hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M,
                                  int32_t* blocks, int32_t* num_blocks, hipStream_t s);
 
+// packed_gu / packed_dn: the projection's region of moe_pack_weights' buffer, or nullptr to
+// read the row-major weights.
 hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
-                          const uint16_t* wu, uint16_t* h, hipStream_t s);
+                          const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s);
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
-                       uint16_t* y_perm, hipStream_t s);
+                       const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s);
+
+size_t packed_gate_up_bytes(const moe_config& c);
+size_t packed_down_bytes(const moe_config& c);
+hipError_t launch_pack(const moe_config& c, const uint16_t* wg, const uint16_t* wu, const uint16_t* wd,
+                       uint16_t* packed, hipStream_t s);
 
 hipError_t launch_combine(const moe_config& c, const uint16_t* y_perm, const int32_t* row_of,
                           const float* topk_w, uint16_t* y, hipStream_t s);

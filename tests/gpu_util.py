@@ -44,6 +44,9 @@ class Layer:
                 self.wg[e].copy_(w[0]); self.wu[e].copy_(w[1]); self.wd[e].copy_(w[2])
         else:
             mi.make_all_experts(s, seed, out=(self.wg, self.wu, self.wd))
+        # one-time packed copy of the expert weights (what a serving stack does at load time)
+        self.packed = torch.empty(moe.packed_weights_size(self.cfg()), dtype=torch.uint8, device=DEV)
+        moe.moe_pack_weights(self.cfg(), self.wg, self.wu, self.wd, self.packed)
         torch.cuda.synchronize()
 
     def cfg(self, tile_m: int = 0, T: int | None = None):
@@ -68,14 +71,18 @@ class Layer:
         return None if self.bias_cpu is None else self.bias_cpu.numpy()
 
 
-def run_forward(layer: Layer, tile_m: int = 0):
-    """moe_forward through the C ABI; returns y bits and every intermediate from the workspace."""
+def run_forward(layer: Layer, tile_m: int = 0, packed: bool = True):
+    """moe_forward through the C ABI; returns y bits and every intermediate from the workspace.
+    packed=True hands the kernels the pre-packed weight copy only (row-major pointers NULL)."""
     cfg = layer.cfg(tile_m)
     s = layer.shape
     lay = moe.forward_workspace_layout(cfg)
     ws = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)
     y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=DEV)
-    moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, layer.wg, layer.wu, layer.wd, y, ws)
+    if packed:
+        moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, None, None, None, y, ws, W_packed=layer.packed)
+    else:
+        moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, layer.wg, layer.wu, layer.wd, y, ws)
     torch.cuda.synchronize()
     R = s.R
 
@@ -134,7 +141,7 @@ def run_block_schedule(cfg, offsets: np.ndarray, M: int):
     return n, blocks.cpu().numpy()[:n], nmax
 
 
-def run_ffn(layer: Layer, cfg, x_perm_bits: np.ndarray, offsets: np.ndarray):
+def run_ffn(layer: Layer, cfg, x_perm_bits: np.ndarray, offsets: np.ndarray, packed: bool = True):
     s = layer.shape
     R = cfg.T * cfg.k
     xp = torch.from_numpy(x_perm_bits.view(np.int16).copy()).view(torch.bfloat16).to(DEV)
@@ -142,7 +149,10 @@ def run_ffn(layer: Layer, cfg, x_perm_bits: np.ndarray, offsets: np.ndarray):
     h = torch.zeros((R, s.F), dtype=torch.bfloat16, device=DEV)
     yp = torch.zeros((R, s.d), dtype=torch.bfloat16, device=DEV)
     ws = torch.zeros(moe.ffn_workspace_size(cfg), dtype=torch.uint8, device=DEV)
-    moe.moe_grouped_ffn(cfg, xp, off, layer.wg, layer.wu, layer.wd, h, yp, ws)
+    if packed:
+        moe.moe_grouped_ffn(cfg, xp, off, None, None, None, h, yp, ws, W_packed=layer.packed)
+    else:
+        moe.moe_grouped_ffn(cfg, xp, off, layer.wg, layer.wu, layer.wd, h, yp, ws)
     torch.cuda.synchronize()
     return np_bits(h), np_bits(yp)
 

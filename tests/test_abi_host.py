@@ -59,15 +59,20 @@ def test_null_alignment_and_workspace_errors_need_no_gpu(L):
     assert L.moe_route(C.byref(c), p + 2, p, None, p, p, None) == -3
     assert L.moe_permute(C.byref(c), p, p, p, p, p, p, p, p, 0, None) == -4
     assert L.moe_permute(C.byref(c), p, p, p, p, p, p, None, p, 1 << 20, None) == -1
-    assert L.moe_grouped_ffn(C.byref(c), p, p, p, p, p, p, p, p, 8, None) == -4
-    assert L.moe_grouped_ffn(C.byref(c), p, p, p, None, p, p, p, p, 1 << 20, None) == -1
+    assert L.moe_grouped_ffn(C.byref(c), p, p, p, p, p, None, p, p, p, 8, None) == -4
+    assert L.moe_grouped_ffn(C.byref(c), p, p, p, None, p, None, p, p, p, 1 << 20, None) == -1
+    assert L.moe_grouped_ffn(C.byref(c), p, p, None, None, None, p + 16, p, p, p, 1 << 20, None) == -3
+    assert L.moe_pack_weights(C.byref(c), p, p, None, p, None) == -1
+    assert L.moe_pack_weights(C.byref(c), p, p, p, p + 16, None) == -3
+    assert moe.packed_weights_size(c) == 6 * c.E * c.d * c.F
     assert L.moe_combine(C.byref(c), p, None, p, p, None) == -1
-    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, p, p, 16, None) == -4
-    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, p + 8, p, 1 << 30, None) == -3
+    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, None, p, p, 16, None) == -4
+    assert L.moe_forward(C.byref(c), p, p, None, p, p, p, None, p + 8, p, 1 << 30, None) == -3
+    assert L.moe_forward(C.byref(c), p, p, None, None, None, None, None, p, p, 1 << 30, None) == -1
     assert L.moe_block_schedule(C.byref(c), p, 0, p, p, None) == -2
     # T == 0 is a no-op that succeeds without a device
     z = moe.MoEConfig.of(0, 256, 512, 8, 2)
-    assert L.moe_forward(C.byref(z), p, p, None, p, p, p, p, p, 1 << 20, None) == 0
+    assert L.moe_forward(C.byref(z), p, p, None, p, p, p, None, p, p, 1 << 20, None) == 0
     assert L.moe_combine(C.byref(z), p, p, p, p, None) == 0
 
 
@@ -98,9 +103,10 @@ def test_max_blocks_bounds_algorithm_1(L):
 
 
 def test_tile_height_choice(L):
-    assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 32      # 16 rows per expert
-    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 128    # 128 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 32      # 16 +- 3.5 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 192    # 128 +- 9.8 rows per expert
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2)) == 256   # 1024 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(512, 7168, 2048, 256, 8)) == 32    # 16 +- 3.9
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2, tile_m=64)) == 64
 
 

@@ -82,10 +82,17 @@ def test_tiny_whole_layer_and_stages(G):
     out = G.run_forward(layer)
     _check_routing(out, ref, layer)
     _check_floats(out, ref, layer, G)
-    # determinism: a second run is bit-identical
+    # determinism: a second run is bit-identical; row-major and packed weights agree bit for bit
+    # (same values, same reduction order)
     out2 = G.run_forward(layer)
+    out3 = G.run_forward(layer, packed=False)
     for key in out:
         assert np.array_equal(out[key], out2[key]), key
+        assert np.array_equal(out[key], out3[key]), key
+    # the packed buffer is a pure permutation of the three weight tensors
+    pk = np.sort(G.np_bits(layer.packed.view(torch.bfloat16)).reshape(-1))
+    raw = np.sort(np.concatenate([G.np_bits(t).reshape(-1) for t in (layer.wg, layer.wu, layer.wd)]))
+    assert np.array_equal(pk, raw)
     # stage entry points one by one, fed with the ORACLE's upstream results
     idx, w = G.run_route(layer)
     assert np.array_equal(idx, ref["topk_idx"]) and np.abs(w - ref["topk_w"]).max() <= 1e-6
@@ -95,10 +102,11 @@ def test_tiny_whole_layer_and_stages(G):
     assert np.array_equal(ro, ref["row_of"]) and np.array_equal(so, ref["src_of"])
     xp_ref = orc.permute_rows(layer.x_bits, ref["src_of"], s.k)
     assert np.array_equal(xp, xp_ref)
-    h_bits, yp_bits = G.run_ffn(layer, cfg, xp_ref, ref["offsets"])
     rows = ref["row_of"].reshape(s.T, s.k)
-    assert _relmax(G.bits_to_f64(h_bits[rows]), ref["h"]) <= REL
-    assert _relmax(G.bits_to_f64(yp_bits[rows]), ref["v"]) <= REL
+    for packed in (True, False):
+        h_bits, yp_bits = G.run_ffn(layer, cfg, xp_ref, ref["offsets"], packed=packed)
+        assert _relmax(G.bits_to_f64(h_bits[rows]), ref["h"]) <= REL
+        assert _relmax(G.bits_to_f64(yp_bits[rows]), ref["v"]) <= REL
     # combine fed with the oracle's FFN outputs rounded to bf16 (input prep, not method arithmetic)
     v_perm = np.zeros((s.R, s.d))
     v_perm[rows.reshape(-1)] = ref["v"].reshape(-1, s.d)
@@ -109,15 +117,16 @@ def test_tiny_whole_layer_and_stages(G):
     assert _relmax(G.bits_to_f64(y_bits), y_ref) <= 2.0 ** -8
 
 
-@pytest.mark.parametrize("tile_m", [32, 64, 128, 256])
-def test_ragged_shape_every_tile_height(G, tile_m):
+@pytest.mark.parametrize("packed", [True, False])
+@pytest.mark.parametrize("tile_m", [32, 64, 96, 128, 160, 192, 256])
+def test_ragged_shape_every_tile_height(G, tile_m, packed):
     """Rows per expert that are no multiple of any tile, feature dims with a ragged last
     feature tile (F=320, d=192), empty experts, and every GEMM variant."""
     s = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
-    _say(f"ragged T=333 d=192 F=320 E=7 k=3 tile_m={tile_m}")
+    _say(f"ragged T=333 d=192 F=320 E=7 k=3 tile_m={tile_m} packed={packed}")
     layer = G.Layer(s, seed=3, skew=2.0)          # strong skew: one expert holds ~T rows, some few
     ref = _oracle_full(layer)
-    out = G.run_forward(layer, tile_m=tile_m)
+    out = G.run_forward(layer, tile_m=tile_m, packed=packed)
     _check_routing(out, ref, layer)
     _check_floats(out, ref, layer, G)
 
@@ -135,15 +144,16 @@ def test_many_experts_small_batches(G, gating):
     _check_floats(out, ref, layer, G)
 
 
+@pytest.mark.parametrize("packed", [True, False])
 @pytest.mark.parametrize("T,E,k", [(1, 8, 2), (2, 4, 4), (65, 1, 1), (1025, 3, 2)])
-def test_degenerate_shapes(G, T, E, k):
+def test_degenerate_shapes(G, T, E, k, packed):
     """Single token, k == E (dense mixture), a single expert, and a token count that crosses the
     permutation kernels' 1024-slot chunk."""
     s = mi.MoEShape("edge", T, 64, 128, E, k, mi.GATE_SOFTMAX)
     _say(f"edge T={T} E={E} k={k}")
     layer = G.Layer(s, seed=7)
     ref = _oracle_full(layer)
-    out = G.run_forward(layer)
+    out = G.run_forward(layer, packed=packed)
     _check_routing(out, ref, layer)
     _check_floats(out, ref, layer, G)
 
@@ -152,7 +162,7 @@ def test_zero_tokens_is_a_noop(G):
     import paper_2605_23911_amd as moe
     cfg = moe.MoEConfig.of(0, 64, 128, 4, 2)
     t = torch.zeros(4096, dtype=torch.uint8, device=G.DEV)
-    moe.moe_forward(cfg, t, t, None, t, t, t, t, t)
+    moe.moe_forward(cfg, t, t, None, t, t, t, t, t, W_packed=t)
     torch.cuda.synchronize()
     assert int(t.sum().item()) == 0
 
@@ -174,7 +184,7 @@ def test_permutation_and_schedule_bit_exact(G, T, E, k, alpha):
     assert np.array_equal(c, c_ref) and np.array_equal(o, o_ref)
     assert np.array_equal(ro, ro_ref) and np.array_equal(so, so_ref)
     assert np.array_equal(xp, orc.permute_rows(G.np_bits(x), so_ref, k))
-    for M in (32, 64, 128, 256):
+    for M in (32, 64, 96, 160, 256):
         n, blocks, nmax = G.run_block_schedule(cfg, o_ref, M)
         want = orc.block_schedule(o_ref, M)
         assert n == len(want) <= nmax
@@ -182,12 +192,12 @@ def test_permutation_and_schedule_bit_exact(G, T, E, k, alpha):
 
 
 # ----------------------------------------------------------------------------- full-size configs, sampled rows
-def _sampled_full_size(G, preset, T, n_tok, skew=0.0):
+def _sampled_full_size(G, preset, T, n_tok, skew=0.0, packed=True):
     s = mi.PRESETS[preset].with_T(T)
     _say(f"{preset} T={T} skew={skew}: generating weights")
     layer = G.Layer(s, seed=0, skew=skew, keep_cpu_weights=False)
-    _say(f"{preset} T={T}: moe_forward")
-    out = G.run_forward(layer)
+    _say(f"{preset} T={T}: moe_forward packed={packed}")
+    out = G.run_forward(layer, packed=packed)
     _say(f"{preset} T={T}: oracle routing on all tokens, FFN on {n_tok} sampled tokens")
     idx_ref, _, _ = orc.route(layer.x_bits, layer.wr_bits, layer.bias_np, s.k, s.gating)
     counts = np.bincount(idx_ref.reshape(-1), minlength=s.E)
@@ -211,6 +221,14 @@ def test_mixtral_T512_bench_configuration(G):
 
 def test_mixtral_T64_weight_bound_regime(G):
     _sampled_full_size(G, "mixtral", 64, 4)
+
+
+def test_mixtral_T512_row_major_weights(G):
+    _sampled_full_size(G, "mixtral", 512, 4, packed=False)
+
+
+def test_mixtral_T4096_mfma_bound_regime(G):
+    _sampled_full_size(G, "mixtral", 4096, 6)
 
 
 def test_qwen2moe_T512_skewed(G):
