@@ -53,6 +53,7 @@ struct GemmArgs {
     const int32_t* blocks;      // [*, 2] (expert, row offset inside the expert)
     const int32_t* num_blocks;  // device scalar
     int R, N, K, n_tiles_n;
+    unsigned long long* dbg;   // MOE_STEP_TIMING builds only
 };
 
 template <int... Is, class F>
@@ -211,27 +212,55 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         });
     };
     // `u` = kt modulo the unroll factor UNR (a multiple of both STAGES and XD), compile-time
+#ifdef MOE_STEP_TIMING
+    unsigned long long tacc[4] = {0, 0, 0, 0};
+#define MOE_TICK(i_) { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[i_] += now_ - tprev; tprev = now_; }
+#else
+#define MOE_TICK(i_)
+#endif
+    // One step.  A wavefront has its SIMD to itself, so whatever it does between MFMAs leaves
+    // the matrix pipe idle unless it is issued while an MFMA is still executing.  The weight
+    // loads of the prefetched step and the LDS fragment reads of the next slot are therefore
+    // spread between the MFMA groups (one group = one weight fragment against all token
+    // blocks); sched_barrier pins that order, which the compiler's scheduler would undo.
     auto step = [&](int kt, auto u) {
         const int buf = kt & 1;
+#ifdef MOE_STEP_TIMING
+        unsigned long long tprev = __builtin_readcyclecounter();
+#endif
+        constexpr int wst = (u + STAGES - 1) % STAGES;
+        const int kw = (kt + STAGES - 1 < KT) ? kt + STAGES - 1 : KT - 1;
         load_x(kt + XD, std::integral_constant<int, (u + XD) % XD>{});           // set (kt+XD)%XD == kt%XD
-        load_w(kt + STAGES - 1, std::integral_constant<int, (u + STAGES - 1) % STAGES>{});
-        __builtin_amdgcn_sched_barrier(0);
-        static_for<4>([&](auto s) {
-            bf16x8 xf[JBE];
-            static_for<JBE>([&](auto j) {
-                xf[j] = *reinterpret_cast<const bf16x8*>(
-                    &xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride + s * 16]);
-            });
-            static_for<NI>([&](auto i) {
-                const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
-                static_for<JBE>([&](auto j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[j], acc[i][j], 0, 0, 0);
-                });
-            });
+        bf16x8 xf[2][JBE];
+        static_for<JBE>([&](auto j) {
+            xf[0][j] = *reinterpret_cast<const bf16x8*>(&xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride]);
         });
         __builtin_amdgcn_sched_barrier(0);
+        MOE_TICK(0)
+        static_for<4>([&](auto s) {
+            static_for<NI>([&](auto i) {
+                wreg[wst][i][s] =
+                    *reinterpret_cast<const uint4*>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                if constexpr (i == 0 && s < 3) {
+                    static_for<JBE>([&](auto j) {
+                        xf[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
+                            &xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride + (s + 1) * 16]);
+                    });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
+                static_for<JBE>([&](auto j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[s & 1][j], acc[i][j], 0, 0, 0);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        MOE_TICK(1)
         store_x(buf ^ 1, std::integral_constant<int, (u + 1) % XD>{});            // token tile of step kt+1
+        __builtin_amdgcn_sched_barrier(0);
+        MOE_TICK(2)
         __syncthreads();
+        MOE_TICK(3)
     };
     // NOTE on register sets: in step kt the set kt%XD is free (its tile, step kt, went to LDS at
     // the end of step kt-1), so the loads of step kt+XD reuse it; with XD == 1 the single set is
@@ -244,12 +273,27 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     __syncthreads();
 
     constexpr int UNR = (STAGES % XD == 0) ? STAGES : STAGES * XD;
+#ifdef MOE_STEP_TIMING
+    const unsigned long long loop_c0 = __builtin_readcyclecounter(), loop_r0 = wall_clock64();
+#endif
     int kt = 0;
     for (; kt + UNR <= KT; kt += UNR) static_for<UNR>([&](auto u) { step(kt + u, u); });
     static_for<UNR>([&](auto u) {
         if (kt + u < KT) step(kt + u, u);
     });
+#ifdef MOE_STEP_TIMING
+    if (a.dbg != nullptr && lane == 0 && wave == 0) {
+        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 0] = __builtin_readcyclecounter() - loop_c0;
+        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 1] = wall_clock64() - loop_r0;
+        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 2] = loop_r0;
+        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 3] = wall_clock64();
+    }
+#endif
 
+#ifdef MOE_STEP_TIMING
+    if (a.dbg != nullptr && lane == 0)
+        for (int q = 0; q < 4; ++q) a.dbg[((size_t)blockIdx.x * 4 + wave) * 4 + q] = tacc[q];
+#endif
     static_for<IB>([&](auto ib) {
         static_for<JBE>([&](auto j) {
             const int tr = j * 32 + li;
@@ -409,6 +453,11 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     }
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
+#ifdef MOE_STEP_TIMING
+    args.dbg = std::getenv(GATEUP ? "MOE_DBG_BUF_GU" : "MOE_DBG_BUF_DN")
+                   ? (unsigned long long*)std::strtoull(std::getenv(GATEUP ? "MOE_DBG_BUF_GU" : "MOE_DBG_BUF_DN"), nullptr, 0)
+                   : nullptr;
+#endif
     const long long grid = (long long)max_blocks * args.n_tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
