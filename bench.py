@@ -162,7 +162,15 @@ def main():
         ach = gate_up_bytes / (gate_up_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": ach / HBM_PEAK_GBS, "traffic": None}
-    roofline.update({"kernel": "grouped_gemm_kernel<gate+up>", "kernel_ms": gate_up_ms,
+    kname = moe.ffn_kernel_name(cfg, 0, packed is not None)
+    try:    # HBM bytes per launch measured with rocprofv3 --pmc for this workload and kernel, if recorded
+        rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get(
+            f"{s.name} T={s.T} {'packed' if packed is not None else 'row-major'}")
+        if rec and rec["kernel"] == kname and args.skew == 0.0 and args.tile_m == 0:
+            roofline["traffic"] = rec["traffic_bytes"]
+    except (OSError, ValueError, KeyError):
+        pass
+    roofline.update({"kernel": kname, "kernel_ms": gate_up_ms,
                      "algorithmic_bytes": gate_up_bytes, "algorithmic_flops": gate_up_flops,
                      "active_experts": e_active})
 
@@ -180,7 +188,7 @@ def main():
         "stages_ms": stages,
     }
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample or 8
+        sample = args.cpu_sample or 256
         result["cpu_baseline"], ref = cpu_baseline(s, x_cpu, wr_cpu, bias_cpu, args.seed, sample)
         yb = y.cpu().view(torch.int16).numpy().view(np.uint16)[ref["tokens"]]
         yg = (yb.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)

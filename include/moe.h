@@ -71,7 +71,7 @@ typedef struct {
     size_t x_perm;    /* bf16  [R,d] */
     size_t h;         /* bf16  [R,F] */
     size_t y_perm;    /* bf16  [R,d] */
-    size_t scratch;   /* internal: chunk histograms, block schedule */
+    size_t scratch;   /* internal: partial logit tiles, chunk histograms, block schedule */
     size_t total;     /* bytes needed */
 } moe_workspace_layout;
 
@@ -84,22 +84,28 @@ const char* moe_status_string(moe_status s);
 int32_t moe_tile_m(const moe_config* cfg);
 
 /* Workspace sizes in bytes (0 for an invalid config).  Host only, no GPU needed. */
+size_t moe_route_workspace_size(const moe_config* cfg);
 size_t moe_permute_workspace_size(const moe_config* cfg);
 size_t moe_ffn_workspace_size(const moe_config* cfg);
 size_t moe_forward_workspace_size(const moe_config* cfg);
 /* Fills *out with the layout moe_forward uses; returns MOE_OK or the config error. */
 moe_status moe_forward_workspace_layout(const moe_config* cfg, moe_workspace_layout* out);
+/* Name of the GEMM kernel instance the library launches for this config (stage 0: fused
+ * gate+up, 1: down; packed != 0: with moe_pack_weights' layout), e.g. for matching profiler
+ * output.  Returns a static string, NULL for an invalid config or stage. */
+const char* moe_ffn_kernel_name(const moe_config* cfg, int32_t stage, int32_t packed);
 /* Upper bound on Alg. 1's block count for tile height M: floor(R/M) + min(E, R). */
 int32_t moe_max_blocks(const moe_config* cfg, int32_t M);
 
 /* Stage 1, router (Eq. 1-2, Sec. 3.4).
  *   x [T,d] bf16, W_r [E,d] bf16, bias [E] fp32 or NULL (added to the logits)
  *   -> topk_idx [T,k] int32, topk_w [T,k] fp32.
- * Logits z = W_r x + bias are accumulated in fp64.  The k experts are chosen by k rounds
- * of arg-max over z with the winner masked; a tie goes to the lower expert index; outputs
- * are in selection order (descending score).  Weights follow cfg->gating. */
+ * Logits z = W_r x + bias are accumulated in fp64 (exact products of the bf16 operands).  The
+ * k experts are chosen by k rounds of arg-max over z with the winner masked; a tie goes to the
+ * lower expert index; outputs are in selection order (descending score).  Weights follow
+ * cfg->gating.  workspace: moe_route_workspace_size(cfg) bytes (partial logit tiles). */
 moe_status moe_route(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
-                     int32_t* topk_idx, float* topk_w, void* stream);
+                     int32_t* topk_idx, float* topk_w, void* workspace, size_t ws_bytes, void* stream);
 
 /* Stage 2, permutation into expert-contiguous order (Sec. 2.2, Sec. 3.5).
  *   topk_idx [T,k] (any valid assignment: values in [0,E), as Sec. 4.7 injects them)

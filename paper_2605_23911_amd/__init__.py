@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     WorkspaceLayout,
     forward_workspace_layout,
     forward_workspace_size,
+    ffn_kernel_name,
     ffn_workspace_size,
     lib,
     library_path,
@@ -27,5 +28,6 @@ from .binding import (  # noqa: F401
     moe_permute,
     moe_route,
     permute_workspace_size,
+    route_workspace_size,
     tile_m,
 )

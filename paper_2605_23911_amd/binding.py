@@ -18,9 +18,9 @@ _LIB_NAME = "libmoe_mi355x.so"
 _lib = None
 
 EXPORTS = (
-    "moe_status_string", "moe_tile_m", "moe_permute_workspace_size", "moe_ffn_workspace_size",
+    "moe_status_string", "moe_tile_m", "moe_route_workspace_size", "moe_permute_workspace_size", "moe_ffn_workspace_size",
     "moe_forward_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
-    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights",
+    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights", "moe_ffn_kernel_name",
 )
 
 
@@ -62,18 +62,20 @@ def lib() -> C.CDLL:
     cfgp, vp, i32p, f32p = C.POINTER(MoEConfig), C.c_void_p, C.c_void_p, C.c_void_p
     L.moe_status_string.restype = C.c_char_p
     L.moe_status_string.argtypes = [C.c_int]
+    L.moe_ffn_kernel_name.restype = C.c_char_p
+    L.moe_ffn_kernel_name.argtypes = [cfgp, C.c_int32, C.c_int32]
     L.moe_tile_m.restype = C.c_int32
     L.moe_tile_m.argtypes = [cfgp]
     L.moe_max_blocks.restype = C.c_int32
     L.moe_max_blocks.argtypes = [cfgp, C.c_int32]
-    for n in ("moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size",
+    for n in ("moe_route_workspace_size", "moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size",
               "moe_packed_weights_size"):
         getattr(L, n).restype = C.c_size_t
         getattr(L, n).argtypes = [cfgp]
     L.moe_forward_workspace_layout.restype = C.c_int
     L.moe_forward_workspace_layout.argtypes = [cfgp, C.POINTER(WorkspaceLayout)]
     L.moe_route.restype = C.c_int
-    L.moe_route.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, vp]
+    L.moe_route.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, vp, C.c_size_t, vp]
     L.moe_permute.restype = C.c_int
     L.moe_permute.argtypes = [cfgp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
     L.moe_block_schedule.restype = C.c_int
@@ -115,12 +117,21 @@ def _nbytes(t) -> int:
     return t.numel() * t.element_size()
 
 
+def ffn_kernel_name(cfg, stage: int, packed: bool) -> str:
+    n = lib().moe_ffn_kernel_name(C.byref(cfg), stage, int(packed))
+    return n.decode() if n else ""
+
+
 def tile_m(cfg) -> int:
     return lib().moe_tile_m(C.byref(cfg))
 
 
 def max_blocks(cfg, M: int) -> int:
     return lib().moe_max_blocks(C.byref(cfg), M)
+
+
+def route_workspace_size(cfg) -> int:
+    return lib().moe_route_workspace_size(C.byref(cfg))
 
 
 def permute_workspace_size(cfg) -> int:
@@ -141,9 +152,9 @@ def forward_workspace_layout(cfg) -> WorkspaceLayout:
     return out
 
 
-def moe_route(cfg, x, W_r, bias, topk_idx, topk_w, stream=None):
+def moe_route(cfg, x, W_r, bias, topk_idx, topk_w, workspace, stream=None):
     _check(lib().moe_route(C.byref(cfg), _ptr(x), _ptr(W_r), _ptr(bias), _ptr(topk_idx), _ptr(topk_w),
-                           _stream(stream)), "moe_route")
+                           _ptr(workspace), _nbytes(workspace), _stream(stream)), "moe_route")
 
 
 def moe_permute(cfg, x, topk_idx, counts, offsets, row_of, src_of, x_perm, workspace, stream=None):

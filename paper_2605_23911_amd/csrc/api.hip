@@ -75,10 +75,20 @@ int32_t moe_tile_m(const moe_config* c) {
     return 256;
 }
 
+const char* moe_ffn_kernel_name(const moe_config* c, int32_t stage, int32_t packed) {
+    if (check_config(c) != MOE_OK || (stage != 0 && stage != 1)) return nullptr;
+    const int M = moe_tile_m(c);
+    return stage == 0 ? gate_up_variant_name(*c, M, packed != 0) : down_variant_name(*c, M, packed != 0);
+}
+
 int32_t moe_max_blocks(const moe_config* c, int32_t M) {
     if (check_config(c) != MOE_OK || M < 1) return 0;
     const long long R = (long long)c->T * c->k;
     return (int32_t)(R / M + (R < c->E ? R : c->E));
+}
+
+size_t moe_route_workspace_size(const moe_config* c) {
+    return check_config(c) == MOE_OK ? align_up(route_workspace_bytes(*c) + 1) : 0;
 }
 
 size_t moe_permute_workspace_size(const moe_config* c) {
@@ -105,7 +115,7 @@ moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layou
     out->x_perm = take(R * c->d * sizeof(uint16_t));
     out->h = take(R * c->F * sizeof(uint16_t));
     out->y_perm = take(R * c->d * sizeof(uint16_t));
-    out->scratch = take(hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
+    out->scratch = take(moe_route_workspace_size(c) + hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
     out->total = off;
     return MOE_OK;
 }
@@ -116,13 +126,14 @@ size_t moe_forward_workspace_size(const moe_config* c) {
 }
 
 moe_status moe_route(const moe_config* c, const void* x, const void* W_r, const float* bias,
-                     int32_t* topk_idx, float* topk_w, void* stream) {
+                     int32_t* topk_idx, float* topk_w, void* workspace, size_t ws_bytes, void* stream) {
     const moe_status st = check_config(c);
     if (st != MOE_OK) return st;
-    if (!x || !W_r || !topk_idx || !topk_w) return MOE_ERR_NULL;
-    if (misaligned(x) || misaligned(W_r)) return MOE_ERR_ALIGN;
+    if (!x || !W_r || !topk_idx || !topk_w || !workspace) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(W_r) || misaligned(workspace)) return MOE_ERR_ALIGN;
+    if (ws_bytes < moe_route_workspace_size(c)) return MOE_ERR_WORKSPACE;
     if (c->T == 0) return MOE_OK;
-    return hip_status(launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w,
+    return hip_status(launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, workspace,
                                    (hipStream_t)stream));
 }
 
@@ -238,9 +249,10 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     uint16_t* x_perm = (uint16_t*)(ws + l.x_perm);
     uint16_t* h = (uint16_t*)(ws + l.h);
     uint16_t* y_perm = (uint16_t*)(ws + l.y_perm);
-    int32_t* hist = (int32_t*)(ws + l.scratch);
+    void* route_ws = ws + l.scratch;
+    int32_t* hist = (int32_t*)(ws + l.scratch + moe_route_workspace_size(c));
     const int M = moe_tile_m(c);
-    int32_t* blocks = (int32_t*)(ws + l.scratch + hist_bytes(c));
+    int32_t* blocks = (int32_t*)((char*)hist + hist_bytes(c));
     int32_t* num_blocks = (int32_t*)((char*)blocks + schedule_bytes(c, M) - kAlign);
 
     hipError_t e = hipSuccess;
@@ -249,7 +261,7 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     };
     mark(0);
     if (e == hipSuccess)
-        e = launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, s);
+        e = launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, route_ws, s);
     mark(1);
     if (e == hipSuccess)
         e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);

@@ -7,30 +7,30 @@ namespace {
 
 const Variant kDown[] = {
     // ---- row-major weights
-    /*0*/ {32, false, launch_skinny<1, false, 4, 1, false>},
-    /*1*/ {32, false, launch_skinny<1, false, 4, 4, false>},
-    /*2*/ {64, false, launch_skinny<2, false, 4, 1, false>},
-    /*3*/ {64, false, launch_skinny<2, false, 4, 4, false>},
-    /*4*/ {96, false, launch_tile<3, 1, false, 4, 2, false, false>},
-    /*5*/ {128, false, launch_tile<4, 1, false, 4, 2, false, false>},
-    /*6*/ {160, false, launch_tile<5, 1, false, 4, 2, false, false>},
-    /*7*/ {192, false, launch_tile<6, 1, false, 4, 2, false, false>},
-    /*8*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false>},
+    /*0*/ {32, false, launch_skinny<1, false, 4, 1, false>, "skinny_kernel<1, false, 4, 1, false>"},
+    /*1*/ {32, false, launch_skinny<1, false, 4, 4, false>, "skinny_kernel<1, false, 4, 4, false>"},
+    /*2*/ {64, false, launch_skinny<2, false, 4, 1, false>, "skinny_kernel<2, false, 4, 1, false>"},
+    /*3*/ {64, false, launch_skinny<2, false, 4, 4, false>, "skinny_kernel<2, false, 4, 4, false>"},
+    /*4*/ {96, false, launch_tile<3, 1, false, 4, 2, false, false>, "tile_kernel<3, 1, false, 4, 2, false, false>"},
+    /*5*/ {128, false, launch_tile<4, 1, false, 4, 2, false, false>, "tile_kernel<4, 1, false, 4, 2, false, false>"},
+    /*6*/ {160, false, launch_tile<5, 1, false, 4, 2, false, false>, "tile_kernel<5, 1, false, 4, 2, false, false>"},
+    /*7*/ {192, false, launch_tile<6, 1, false, 4, 2, false, false>, "tile_kernel<6, 1, false, 4, 2, false, false>"},
+    /*8*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false>, "tile_kernel<8, 1, false, 3, 1, true, false>"},
     // ---- packed weights
-    /*9*/ {32, true, launch_skinny<1, false, 4, 1, true>},
-    /*10*/ {32, true, launch_skinny<1, false, 4, 4, true>},
-    /*11*/ {32, true, launch_tile<1, 1, false, 6, 3, false, true>},
-    /*12*/ {64, true, launch_skinny<2, false, 4, 4, true>},
-    /*13*/ {64, true, launch_tile<2, 1, false, 4, 2, false, true>},
-    /*14*/ {96, true, launch_tile<3, 1, false, 4, 2, false, true>},
-    /*15*/ {128, true, launch_tile<4, 1, false, 4, 2, false, true>},
-    /*16*/ {160, true, launch_tile<5, 1, false, 4, 2, false, true>},
-    /*17*/ {192, true, launch_tile<6, 1, false, 4, 2, false, true>},
-    /*18*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true>},
-    /*19*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true>},
-    /*20*/ {128, true, launch_tile<4, 2, false, 3, 2, false, true>},
-    /*21*/ {128, true, launch_tile<4, 4, false, 2, 1, false, true>},
-    /*22*/ {192, true, launch_tile<6, 2, false, 3, 2, false, true>},
+    /*9*/ {32, true, launch_skinny<1, false, 4, 1, true>, "skinny_kernel<1, false, 4, 1, true>"},
+    /*10*/ {32, true, launch_skinny<1, false, 4, 4, true>, "skinny_kernel<1, false, 4, 4, true>"},
+    /*11*/ {32, true, launch_tile<1, 1, false, 6, 3, false, true>, "tile_kernel<1, 1, false, 6, 3, false, true>"},
+    /*12*/ {64, true, launch_skinny<2, false, 4, 4, true>, "skinny_kernel<2, false, 4, 4, true>"},
+    /*13*/ {64, true, launch_tile<2, 1, false, 4, 2, false, true>, "tile_kernel<2, 1, false, 4, 2, false, true>"},
+    /*14*/ {96, true, launch_tile<3, 1, false, 4, 2, false, true>, "tile_kernel<3, 1, false, 4, 2, false, true>"},
+    /*15*/ {128, true, launch_tile<4, 1, false, 4, 2, false, true>, "tile_kernel<4, 1, false, 4, 2, false, true>"},
+    /*16*/ {160, true, launch_tile<5, 1, false, 4, 2, false, true>, "tile_kernel<5, 1, false, 4, 2, false, true>"},
+    /*17*/ {192, true, launch_tile<6, 1, false, 4, 2, false, true>, "tile_kernel<6, 1, false, 4, 2, false, true>"},
+    /*18*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true>, "tile_kernel<8, 1, false, 4, 2, true, true>"},
+    /*19*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true>, "tile_kernel<8, 2, false, 2, 1, true, true>"},
+    /*20*/ {128, true, launch_tile<4, 2, false, 3, 2, false, true>, "tile_kernel<4, 2, false, 3, 2, false, true>"},
+    /*21*/ {128, true, launch_tile<4, 4, false, 2, 1, false, true>, "tile_kernel<4, 4, false, 2, 1, false, true>"},
+    /*22*/ {192, true, launch_tile<6, 2, false, 3, 2, false, true>, "tile_kernel<6, 2, false, 3, 2, false, true>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -64,6 +64,12 @@ int pick(int M, bool packed, const moe_config& c) {
 }
 
 }  // namespace
+
+const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
+    int id = env_variant("MOE_DN_VARIANT", kNumDown, M, packed, kDown);
+    if (id < 0) id = pick(M, packed, c);
+    return kDown[id].name;
+}
 
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,

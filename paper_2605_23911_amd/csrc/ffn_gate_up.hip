@@ -9,26 +9,26 @@ namespace {
 // skinny<JB, gateup, STAGES, SPLITK, packed>.
 const Variant kGateUp[] = {
     // ---- row-major weights
-    /*0*/ {32, false, launch_skinny<1, true, 4, 1, false>},
-    /*1*/ {64, false, launch_skinny<2, true, 3, 1, false>},
-    /*2*/ {96, false, launch_tile<3, 1, true, 3, 1, false, false>},
-    /*3*/ {128, false, launch_tile<4, 1, true, 3, 1, false, false>},
-    /*4*/ {160, false, launch_tile<5, 1, true, 3, 1, false, false>},
-    /*5*/ {192, false, launch_tile<6, 1, true, 3, 1, false, false>},
-    /*6*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false>},
+    /*0*/ {32, false, launch_skinny<1, true, 4, 1, false>, "skinny_kernel<1, true, 4, 1, false>"},
+    /*1*/ {64, false, launch_skinny<2, true, 3, 1, false>, "skinny_kernel<2, true, 3, 1, false>"},
+    /*2*/ {96, false, launch_tile<3, 1, true, 3, 1, false, false>, "tile_kernel<3, 1, true, 3, 1, false, false>"},
+    /*3*/ {128, false, launch_tile<4, 1, true, 3, 1, false, false>, "tile_kernel<4, 1, true, 3, 1, false, false>"},
+    /*4*/ {160, false, launch_tile<5, 1, true, 3, 1, false, false>, "tile_kernel<5, 1, true, 3, 1, false, false>"},
+    /*5*/ {192, false, launch_tile<6, 1, true, 3, 1, false, false>, "tile_kernel<6, 1, true, 3, 1, false, false>"},
+    /*6*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false>, "tile_kernel<8, 1, true, 2, 1, true, false>"},
     // ---- packed weights
-    /*7*/ {32, true, launch_skinny<1, true, 4, 1, true>},
-    /*8*/ {32, true, launch_tile<1, 1, true, 4, 2, false, true>},
-    /*9*/ {64, true, launch_skinny<2, true, 3, 1, true>},
-    /*10*/ {64, true, launch_tile<2, 1, true, 4, 2, false, true>},
-    /*11*/ {96, true, launch_tile<3, 1, true, 4, 2, false, true>},
-    /*12*/ {128, true, launch_tile<4, 1, true, 4, 2, false, true>},
-    /*13*/ {160, true, launch_tile<5, 1, true, 4, 2, false, true>},
-    /*14*/ {192, true, launch_tile<6, 1, true, 4, 2, false, true>},
-    /*15*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true>},
-    /*16*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>},
-    /*17*/ {160, true, launch_tile<5, 1, true, 3, 1, false, true>},
-    /*18*/ {32, true, launch_skinny<1, true, 6, 1, true>},
+    /*7*/ {32, true, launch_skinny<1, true, 4, 1, true>, "skinny_kernel<1, true, 4, 1, true>"},
+    /*8*/ {32, true, launch_tile<1, 1, true, 4, 2, false, true>, "tile_kernel<1, 1, true, 4, 2, false, true>"},
+    /*9*/ {64, true, launch_skinny<2, true, 3, 1, true>, "skinny_kernel<2, true, 3, 1, true>"},
+    /*10*/ {64, true, launch_tile<2, 1, true, 4, 2, false, true>, "tile_kernel<2, 1, true, 4, 2, false, true>"},
+    /*11*/ {96, true, launch_tile<3, 1, true, 4, 2, false, true>, "tile_kernel<3, 1, true, 4, 2, false, true>"},
+    /*12*/ {128, true, launch_tile<4, 1, true, 4, 2, false, true>, "tile_kernel<4, 1, true, 4, 2, false, true>"},
+    /*13*/ {160, true, launch_tile<5, 1, true, 4, 2, false, true>, "tile_kernel<5, 1, true, 4, 2, false, true>"},
+    /*14*/ {192, true, launch_tile<6, 1, true, 4, 2, false, true>, "tile_kernel<6, 1, true, 4, 2, false, true>"},
+    /*15*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true>, "tile_kernel<8, 1, true, 2, 1, true, true>"},
+    /*16*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>, "tile_kernel<4, 2, true, 2, 1, false, true>"},
+    /*17*/ {160, true, launch_tile<5, 1, true, 3, 1, false, true>, "tile_kernel<5, 1, true, 3, 1, false, true>"},
+    /*18*/ {32, true, launch_skinny<1, true, 6, 1, true>, "skinny_kernel<1, true, 6, 1, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
@@ -56,6 +56,12 @@ int pick(int M, bool packed) {
 }
 
 }  // namespace
+
+const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed) {
+    int id = env_variant("MOE_GU_VARIANT", kNumGateUp, M, packed, kGateUp);
+    if (id < 0) id = pick(M, packed);
+    return kGateUp[id].name;
+}
 
 hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,

@@ -478,6 +478,7 @@ struct Variant {
     int M;          // tile height (Alg. 1's M) this variant implements
     bool packed;    // consumes moe_pack_weights' layout
     launch_fn fn;
+    const char* name;   // kernel template instance, as rocprofv3 prints it (minus namespaces)
 };
 
 // A tuning run may force a variant by table index through an environment variable; the index

@@ -32,8 +32,10 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
 }
 
 // ---- launchers (each enqueues on `s` and returns hipGetLastError()) ----------------------
+// workspace: route_workspace_bytes(c) bytes of fp64 partial logit tiles
+size_t route_workspace_bytes(const moe_config& c);
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, hipStream_t s);
+                        int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s);
 
 // scratch: chunk histograms [nchunks, E] int32.  If blocks != nullptr the block schedule for
 // tile height M is emitted by the scan kernel as well.
@@ -53,6 +55,9 @@ hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s);
+
+const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed);
+const char* down_variant_name(const moe_config& c, int32_t M, bool packed);
 
 size_t packed_gate_up_bytes(const moe_config& c);
 size_t packed_down_bytes(const moe_config& c);

@@ -1,17 +1,32 @@
-// Router: logits z = W_r x (+ bias) in fp64, softmax / sigmoid gate, wavefront top-k.
-// Paper: Eq. 1 and Eq. 2 (Sec. 2.1); Sec. 3.4 (max-subtracted softmax, iterative arg-max
-// with the winner masked, softmax and sigmoid gating).  Unlike the paper the projection is
-// part of this kernel, and the arg-max runs on the logits with an explicit "already chosen"
-// mask instead of overwriting scores with -1.
+// Router: logits z = W_r x (+ bias) in fp64 on the fp64 matrix cores, then softmax / sigmoid
+// gate and a wavefront top-k.
+// Paper: Eq. 1 and Eq. 2 (Sec. 2.1); Sec. 3.4 (max-subtracted softmax, iterative arg-max with
+// the winner masked, softmax and sigmoid gating).  Unlike the paper the projection is part of
+// this stage (no library GEMM), and the arg-max runs on the logits with an explicit
+// "already chosen" mask instead of overwriting scores with -1.
+//
+// Why fp64: the expert indices must equal those of an exact evaluation.  With hundreds of
+// experts and thousands of tokens the smallest gap between neighbouring top-(k+1) logits is of
+// the order of 1e-6, below what an fp32-accumulated dot product of length d resolves.  bf16
+// operands convert exactly to fp64 and their products are exact there, so the fp64 MFMA
+// (v_mfma_f64_16x16x4) gives logits good to ~1e-15 at the fp64 matrix rate.
+//
+// Kernel 1 (logits): one wavefront per work unit (16 tokens x 16 experts x one slice of d).
+//   The reduction is cut into enough slices to put >= ~2000 wavefronts on the chip even for
+//   one token and eight experts; each unit writes its 16x16 fp64 partial tile.
+// Kernel 2 (gate + top-k): one wavefront per token sums the slices, applies the gate and
+//   selects k experts.
 #include "moe_internal.hpp"
 
 namespace moe {
 
 namespace {
 
-constexpr int kRouteTokens = 4;   // tokens per workgroup == wavefronts per workgroup
-constexpr int kRouteDC = 2048;    // elements of d staged in LDS per pass
-constexpr int kRouteThreads = kRouteTokens * kWave;
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kWavesPerBlock = kThreads / kWave;
+constexpr int kChunk = 32;   // reduction elements per chunk: 4 lane groups x 8 consecutive k
 
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
@@ -34,70 +49,89 @@ __device__ __forceinline__ void unpack8(const uint4& v, double* out) {
     }
 }
 
-__global__ __launch_bounds__(kRouteThreads) void route_kernel(
-    const uint16_t* __restrict__ x, const uint16_t* __restrict__ wr, const float* __restrict__ bias,
-    int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, int T, int d, int E, int k, int gating) {
-    __shared__ uint4 xs[kRouteTokens][kRouteDC / 8];
-    __shared__ double zs[kRouteTokens][kMaxExperts];
-    __shared__ int32_t sel_idx[kRouteTokens][kMaxExperts];
+// ---- kernel 1: partial logit tiles ----------------------------------------------------------
+// part[ks][t][e], t < T16*16, e < E16*16 (padded to whole tiles).
+// MFMA operand layout (v_mfma_f64_16x16x4): lane l supplies A[i = l%16][k = l/16] and
+// B[k = l/16][j = l%16]; it receives D[i = l/16 + 4v][j = l%16], v = 0..3.  The MFMA sums over
+// k, so which k a slot carries is free as long as A and B agree: lane group g = l/16 loads 8
+// consecutive k (one 16-byte load) and the q-th MFMA of a chunk takes element q of every lane.
+__global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __restrict__ x,
+                                                         const uint16_t* __restrict__ wr,
+                                                         double* __restrict__ part, int T, int d, int E, int T16,
+                                                         int E16, int KS, int units) {
+    const int lane = threadIdx.x % kWave;
+    const int unit = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
+    if (unit >= units) return;
+    const int ks = unit % KS;
+    const int et = (unit / KS) % E16;
+    const int tt = unit / (KS * E16);
+    const int i = lane & 15, g = lane >> 4;
 
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
-    const int t0 = blockIdx.x * kRouteTokens;
+    const int nchunk = d / kChunk;
+    const int per = (nchunk + KS - 1) / KS;
+    const int c0 = ks * per;
+    const int c1 = (c0 + per) < nchunk ? (c0 + per) : nchunk;
 
-    for (int i = tid; i < kRouteTokens * E; i += kRouteThreads) {
-        const int e = i % E;
-        zs[i / E][e] = bias ? (double)bias[e] : 0.0;
-    }
+    const int trow = (tt * 16 + i) < T ? (tt * 16 + i) : (T - 1);
+    const int erow = (et * 16 + i) < E ? (et * 16 + i) : (E - 1);
+    const uint16_t* xp = x + (size_t)trow * d + g * 8;
+    const uint16_t* wp = wr + (size_t)erow * d + g * 8;
 
-    // ---- logits: every wavefront owns the experts e = wave (mod 4); lanes stride over d.
-    for (int c0 = 0; c0 < d; c0 += kRouteDC) {
-        const int cv = ((d - c0) < kRouteDC ? (d - c0) : kRouteDC) / 8;   // 16-byte vectors in this pass
-        __syncthreads();
-        for (int v = tid; v < kRouteTokens * cv; v += kRouteThreads) {
-            const int tt = v / cv, j = v % cv;
-            const int t = (t0 + tt < T) ? (t0 + tt) : (T - 1);
-            xs[tt][j] = *reinterpret_cast<const uint4*>(x + (size_t)t * d + c0 + j * 8);
-        }
-        __syncthreads();
-        for (int e = wave; e < E; e += kRouteTokens) {
-            double acc[kRouteTokens];
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    if (c0 < c1) {
+        uint4 xr = *reinterpret_cast<const uint4*>(xp + (size_t)c0 * kChunk);
+        uint4 wv = *reinterpret_cast<const uint4*>(wp + (size_t)c0 * kChunk);
+        for (int c = c0; c < c1; ++c) {
+            const int cn = (c + 1 < c1) ? c + 1 : c;   // prefetch (the last chunk re-reads itself)
+            const uint4 xn = *reinterpret_cast<const uint4*>(xp + (size_t)cn * kChunk);
+            const uint4 wn = *reinterpret_cast<const uint4*>(wp + (size_t)cn * kChunk);
+            double a8[8], b8[8];
+            unpack8(xr, a8);
+            unpack8(wv, b8);
 #pragma unroll
-            for (int tt = 0; tt < kRouteTokens; ++tt) acc[tt] = 0.0;
-            const uint16_t* wrow = wr + (size_t)e * d + c0;
-            for (int j = lane; j < cv; j += kWave) {
-                double w8[8];
-                unpack8(*reinterpret_cast<const uint4*>(wrow + j * 8), w8);
-#pragma unroll
-                for (int tt = 0; tt < kRouteTokens; ++tt) {
-                    double x8[8];
-                    unpack8(xs[tt][j], x8);
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) acc[tt] = fma(x8[q], w8[q], acc[tt]);
-                }
-            }
-#pragma unroll
-            for (int tt = 0; tt < kRouteTokens; ++tt) acc[tt] = wave_sum(acc[tt]);
-            if (lane == 0) {
-#pragma unroll
-                for (int tt = 0; tt < kRouteTokens; ++tt) zs[tt][e] += acc[tt];
-            }
+            for (int q = 0; q < 8; ++q) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a8[q], b8[q], acc, 0, 0, 0);
+            xr = xn;
+            wv = wn;
         }
     }
-    __syncthreads();
+    const size_t EP = (size_t)E16 * 16;
+    double* out = part + ((size_t)ks * T16 * 16 + (size_t)tt * 16) * EP + (size_t)et * 16 + i;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) out[(size_t)(g + 4 * v) * EP] = acc[v];
+}
 
-    // ---- gate + top-k: wavefront `wave` finishes token t0 + wave.
-    const int t = t0 + wave;
+// ---- kernel 2: gate + top-k, one wavefront per token ------------------------------------------
+__global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict__ part,
+                                                       const float* __restrict__ bias,
+                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                       int T, int E, int k, int gating, int T16, int E16, int KS) {
+    __shared__ double wsel[kWavesPerBlock][kMaxExperts];
+    __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * kWavesPerBlock + wave;
     if (t >= T) return;
 
     constexpr int Q = kMaxExperts / kWave;   // logits per lane
     const double ninf = -__builtin_huge_val();
+    const size_t EP = (size_t)E16 * 16;
     double z[Q], p[Q];
     bool ok[Q];
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
         const int e = lane + kWave * q;
         ok[q] = e < E;
-        double v = ok[q] ? zs[wave][e] : ninf;
+        double v = ninf;
+        if (ok[q]) {
+            v = bias ? (double)bias[e] : 0.0;
+            for (int s0 = 0; s0 < KS; s0 += 8) {   // slices in fixed order; 8 independent loads at a time
+                double tmp[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    tmp[u] = (s0 + u < KS) ? part[((size_t)(s0 + u) * T16 * 16 + t) * EP + e] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v += tmp[u];
+            }
+        }
         z[q] = (v != v) ? ninf : v;   // a NaN logit can never win and never breaks the index range
     }
     double m = ninf;
@@ -151,24 +185,52 @@ __global__ __launch_bounds__(kRouteThreads) void route_kernel(
         wsum += wv;
         if (lane == 0) {
             sel_idx[wave][r] = be;
-            zs[wave][r] = wv;   // the logit row lives in registers by now; reuse its LDS row
+            wsel[wave][r] = wv;
         }
     }
     const double scale = (gating == MOE_GATE_SOFTMAX) ? 1.0 : 1.0 / wsum;
     __builtin_amdgcn_wave_barrier();
     for (int i = lane; i < k; i += kWave) {
         topk_idx[(size_t)t * k + i] = *(volatile int32_t*)&sel_idx[wave][i];
-        topk_w[(size_t)t * k + i] = (float)(*(volatile double*)&zs[wave][i] * scale);
+        topk_w[(size_t)t * k + i] = (float)(*(volatile double*)&wsel[wave][i] * scale);
     }
+}
+
+struct RoutePlan {
+    int T16, E16, KS;
+};
+
+RoutePlan plan(const moe_config& c) {
+    RoutePlan p;
+    p.T16 = (c.T + 15) / 16;
+    p.E16 = (c.E + 15) / 16;
+    const long long tiles = (long long)p.T16 * p.E16;
+    const int nchunk = c.d / kChunk;
+    long long ks = (2048 + tiles - 1) / tiles;          // aim for >= ~2048 wavefronts
+    if (ks > 16) ks = 16;                               // the top-k kernel sums the slices serially
+    if (ks > nchunk / 2) ks = nchunk / 2;               // at least two chunks per slice
+    if (ks < 1) ks = 1;
+    p.KS = (int)ks;
+    return p;
 }
 
 }  // namespace
 
+size_t route_workspace_bytes(const moe_config& c) {
+    if (c.T == 0) return 0;
+    const RoutePlan p = plan(c);
+    return (size_t)p.KS * p.T16 * 16 * p.E16 * 16 * sizeof(double);
+}
+
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, hipStream_t s) {
-    const int grid = (c.T + kRouteTokens - 1) / kRouteTokens;
-    hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(kRouteThreads), 0, s, x, wr, bias, topk_idx, topk_w,
-                       c.T, c.d, c.E, c.k, c.gating);
+                        int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s) {
+    const RoutePlan p = plan(c);
+    const int units = p.T16 * p.E16 * p.KS;
+    double* part = (double*)workspace;
+    hipLaunchKernelGGL(logits_kernel, dim3((units + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kThreads), 0, s, x,
+                       wr, part, c.T, c.d, c.E, p.T16, p.E16, p.KS, units);
+    hipLaunchKernelGGL(topk_kernel, dim3((c.T + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kThreads), 0, s, part,
+                       bias, topk_idx, topk_w, c.T, c.E, c.k, c.gating, p.T16, p.E16, p.KS);
     return hipGetLastError();
 }
 

@@ -109,7 +109,8 @@ def run_route(layer: Layer):
     s = layer.shape
     idx = torch.full((s.T, s.k), -7, dtype=torch.int32, device=DEV)
     w = torch.zeros((s.T, s.k), dtype=torch.float32, device=DEV)
-    moe.moe_route(cfg, layer.x, layer.wr, layer.bias, idx, w)
+    ws = torch.zeros(max(moe.route_workspace_size(cfg), 256), dtype=torch.uint8, device=DEV)
+    moe.moe_route(cfg, layer.x, layer.wr, layer.bias, idx, w, ws)
     torch.cuda.synchronize()
     return idx.cpu().numpy(), w.cpu().numpy()
 

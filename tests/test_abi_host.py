@@ -46,17 +46,19 @@ def test_config_validation(L):
     for c in bad:
         assert moe.tile_m(c) == 0 and moe.forward_workspace_size(c) == 0
         assert moe.permute_workspace_size(c) == 0 and moe.ffn_workspace_size(c) == 0
-    st = L.moe_route(C.byref(bad[1]), 16, 16, None, 16, 16, None)
+    st = L.moe_route(C.byref(bad[1]), 16, 16, None, 16, 16, 16, 1 << 20, None)
     assert st == -2
-    assert L.moe_route(C.byref(bad[3]), 16, 16, None, 16, 16, None) == -5
-    assert L.moe_route(C.byref(bad[4]), 16, 16, None, 16, 16, None) == -5
+    assert L.moe_route(C.byref(bad[3]), 16, 16, None, 16, 16, 16, 1 << 20, None) == -5
+    assert L.moe_route(C.byref(bad[4]), 16, 16, None, 16, 16, 16, 1 << 20, None) == -5
 
 
 def test_null_alignment_and_workspace_errors_need_no_gpu(L):
     c = moe.MoEConfig.of(64, 256, 512, 8, 2)
     p = 4096   # never dereferenced: every call below must fail on the host
-    assert L.moe_route(C.byref(c), None, p, None, p, p, None) == -1
-    assert L.moe_route(C.byref(c), p + 2, p, None, p, p, None) == -3
+    assert L.moe_route(C.byref(c), None, p, None, p, p, p, 1 << 20, None) == -1
+    assert L.moe_route(C.byref(c), p + 2, p, None, p, p, p, 1 << 20, None) == -3
+    assert L.moe_route(C.byref(c), p, p, None, p, p, p, 8, None) == -4
+    assert moe.route_workspace_size(c) >= 8 * 64 * 16
     assert L.moe_permute(C.byref(c), p, p, p, p, p, p, p, p, 0, None) == -4
     assert L.moe_permute(C.byref(c), p, p, p, p, p, p, None, p, 1 << 20, None) == -1
     assert L.moe_grouped_ffn(C.byref(c), p, p, p, p, p, None, p, p, p, 8, None) == -4
@@ -85,8 +87,8 @@ def test_workspace_layout_is_ordered_and_sized(L):
         assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
         R = T * k
         assert l.h - l.x_perm >= R * d * 2 and l.y_perm - l.h >= R * F * 2
-        assert l.total == moe.forward_workspace_size(c) >= l.scratch + moe.ffn_workspace_size(c)
-        assert l.total < 2 * R * (2 * d + F) + (1 << 20) + 16 * R + 4 * E * (R // 1024 + 1) * 2
+        assert l.total == moe.forward_workspace_size(c) >= l.scratch + moe.ffn_workspace_size(c) + moe.route_workspace_size(c)
+        assert l.total < 2 * R * (2 * d + F) + (8 << 20) + 16 * R + 4 * E * (R // 1024 + 1) * 2 + 8 * (T + 16) * (E + 16)
 
 
 def test_max_blocks_bounds_algorithm_1(L):
