@@ -79,7 +79,7 @@ const char* moe_status_string(moe_status s);
 
 /* Tile height (Alg. 1's M) the library uses for this config: cfg->tile_m if non-zero
  * (must be 32, 64, 96, 128, 160, 192 or 256), else the smallest of these that holds the mean
- * rows per expert T*k/E plus four standard deviations of uniform routing (256 beyond that).
+ * rows per expert T*k/E plus three standard deviations of uniform routing (256 beyond that).
  * Returns 0 for an invalid config. */
 int32_t moe_tile_m(const moe_config* cfg);
 

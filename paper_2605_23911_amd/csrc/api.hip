@@ -66,10 +66,12 @@ int32_t moe_tile_m(const moe_config* c) {
     if (check_config(c) != MOE_OK) return 0;
     if (c->tile_m != 0) return c->tile_m;
     // Rows per expert under near-uniform routing are Binomial(T, k/E): take the smallest tile
-    // that holds mean + 4 sigma, so that (almost) every expert is ONE tile and its weights are
-    // streamed once.  Beyond 192 rows the 256-row tile skips its empty 64-row groups itself.
+    // that holds mean + 3 sigma, so that nearly every expert is ONE tile and its weights are
+    // streamed once (an expert beyond that simply gets a second, short tile).  Smaller tiles
+    // mean fewer MFMAs on padding rows, which matters because sustained MFMA work lowers the
+    // clock.  Beyond 192 rows the 256-row tile skips its empty 64-row groups itself.
     const double p = (double)c->k / c->E;
-    const double need = c->T * p + 4.0 * sqrt(c->T * p * (1.0 - p));
+    const double need = c->T * p + 3.0 * sqrt(c->T * p * (1.0 - p));
     for (int v : kTileHeights)
         if (need <= v && v < 256) return v;
     return 256;

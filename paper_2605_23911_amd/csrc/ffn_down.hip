@@ -31,6 +31,11 @@ const Variant kDown[] = {
     /*20*/ {128, true, launch_tile<4, 2, false, 3, 2, false, true>, "tile_kernel<4, 2, false, 3, 2, false, true>"},
     /*21*/ {128, true, launch_tile<4, 4, false, 2, 1, false, true>, "tile_kernel<4, 4, false, 2, 1, false, true>"},
     /*22*/ {192, true, launch_tile<6, 2, false, 3, 2, false, true>, "tile_kernel<6, 2, false, 3, 2, false, true>"},
+    /*23*/ {192, true, launch_tile<6, 1, false, 4, 2, false, true, 8>, "tile_kernel<6, 1, false, 4, 2, false, true, 8>"},
+    /*24*/ {192, true, launch_tile<6, 2, false, 3, 2, false, true, 8>, "tile_kernel<6, 2, false, 3, 2, false, true, 8>"},
+    /*25*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 8>, "tile_kernel<8, 2, false, 2, 1, true, true, 8>"},
+    /*26*/ {256, true, launch_tile<8, 2, false, 3, 2, true, true, 8>, "tile_kernel<8, 2, false, 3, 2, true, true, 8>"},
+    /*27*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true, 8>, "tile_kernel<8, 1, false, 4, 2, true, true, 8>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 

@@ -29,6 +29,12 @@ const Variant kGateUp[] = {
     /*16*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>, "tile_kernel<4, 2, true, 2, 1, false, true>"},
     /*17*/ {160, true, launch_tile<5, 1, true, 3, 1, false, true>, "tile_kernel<5, 1, true, 3, 1, false, true>"},
     /*18*/ {32, true, launch_skinny<1, true, 6, 1, true>, "skinny_kernel<1, true, 6, 1, true>"},
+    /*19*/ {192, true, launch_tile<6, 1, true, 3, 1, false, true, 8>, "tile_kernel<6, 1, true, 3, 1, false, true, 8>"},
+    /*20*/ {192, true, launch_tile<6, 1, true, 2, 1, false, true, 8>, "tile_kernel<6, 1, true, 2, 1, false, true, 8>"},
+    /*21*/ {192, true, launch_tile<6, 1, true, 3, 2, false, true, 8>, "tile_kernel<6, 1, true, 3, 2, false, true, 8>"},
+    /*22*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 8>, "tile_kernel<8, 1, true, 2, 1, true, true, 8>"},
+    /*23*/ {256, true, launch_tile<8, 1, true, 3, 1, true, true, 8>, "tile_kernel<8, 1, true, 3, 1, true, true, 8>"},
+    /*24*/ {128, true, launch_tile<4, 1, true, 4, 2, false, true, 8>, "tile_kernel<4, 1, true, 4, 2, false, true, 8>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 

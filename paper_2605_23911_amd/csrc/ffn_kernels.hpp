@@ -141,54 +141,77 @@ __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, ui
 
 // =============================================================================================
 // tile_kernel: JB*32 token rows in LDS, IB 32-row weight blocks per wavefront and matrix.
+// NW = 4: four wavefronts, each owning its weight rows and ALL token rows of the tile.
+// NW = 8: the token rows are split in two halves; wavefronts w and w+4 own the same weight rows
+//         (both load them: the second load hits L1) and one half of the tokens each.  Half the
+//         accumulators per wavefront -> two wavefronts per SIMD, so one wavefront's load issue,
+//         LDS waits and barrier overlap with the other's MFMAs.
 // =============================================================================================
-template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED>
+template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, int NW>
 __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NM = GATEUP ? 2 : 1;
     constexpr int NI = IB * NM;
     constexpr int BM = JB * 32;
     constexpr int BN = 4 * IB * 32;
+    constexpr int TH = NW / 4;                  // token groups (1 or 2)
+    constexpr int JW = JBE / TH;                // 32-row token blocks per wavefront
+    constexpr int NTHR = NW * kWave;
+    constexpr int XROWS = NTHR / 8;             // token rows staged per pass (8 threads x 16 B per row)
+    constexpr int XP = (JBE * 32) / XROWS;      // passes per step
+    static_assert(JBE % TH == 0 && (JBE * 32) % XROWS == 0, "token tile must split evenly");
     const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
     const int li = lane & 31, half = lane >> 5;
+    const int wrow = wave & 3, tgrp = wave >> 2;
     const int K = a.K, N = a.N;
     const int KT = K / kBK;
-    const int n0w = nt * BN + wave * (IB * 32);
+    const int n0w = nt * BN + wrow * (IB * 32);
 
     typedef WAddr<PACKED, NM> WA;
     const uint16_t* wp[NI];   // out-of-range rows of a ragged last feature tile are clamped, stores masked
     static_for<NM>([&](auto m) {
         static_for<IB>([&](auto ib) { wp[m * IB + ib] = WA::base(a, t.e, n0w / 32 + ib, m, lane); });
     });
-    // token tile: thread -> (row tid/8 + 32p, 16-byte chunk tid%8); rows clamped inside X
-    const uint16_t* xp[JBE];
-    static_for<JBE>([&](auto p) {
-        int row = t.row0 + (tid >> 3) + 32 * p;
+    // token tile: thread -> (row tid/8 + XROWS*p, 16-byte chunk tid%8); rows clamped inside X
+    const uint16_t* xp[XP];
+    static_for<XP>([&](auto p) {
+        int row = t.row0 + (tid >> 3) + XROWS * p;
         row = row < a.R ? row : a.R - 1;
         xp[p] = a.X + (size_t)row * K + (tid & 7) * 8;
     });
     const int xs_store = (tid >> 3) * kLdsStride + (tid & 7) * 8;
-    const int xs_read = li * kLdsStride + half * 8;
+    const int xs_read = (tgrp * JW * 32 + li) * kLdsStride + half * 8;
 
-    f32x16 acc[NI][JBE];
+    f32x16 acc[NI][JW];
     static_for<NI>([&](auto i) {
-        static_for<JBE>([&](auto j) {
+        static_for<JW>([&](auto j) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         });
     });
 
     uint4 wreg[STAGES][NI][4];
-    typedef uint32_t xreg_t __attribute__((ext_vector_type(4 * JBE)));
+    typedef uint32_t xreg_t __attribute__((ext_vector_type(4 * XP)));
     xreg_t xreg[XD];   // each set is one SSA vector value (a plain array is not reliably kept in registers)
 
-    // Software pipeline.  In step kt the wavefront issues, in this order, the token-tile loads
-    // of step kt+XD and the weight loads of step kt+STAGES-1, runs the MFMAs of step kt from
-    // LDS buffer kt%2 and its weight registers, then writes the token tile of step kt+1 (loaded
-    // XD-1 steps ago) into the other LDS buffer.  Loads complete in issue order, so that last
-    // wait leaves everything issued later in flight.  All loads are unconditional (the step
-    // index is clamped to the last step, which is re-read harmlessly): straight-line code.
+    // The K loop is rotated per workgroup: logical step i reads physical step (i + rot) mod KT.
+    // All rows of a token tile at one k step are a whole multiple of 4 KiB apart when the row
+    // length is (d = 4096, F = 14336, ...), so they sit in the same L2 channel; workgroups that
+    // run together on an XCD (ids 8 apart) start two steps apart and so spread over the channels
+    // instead of all hammering the same one.  The sum over k does not care about the order.
+    const int rot = (int)(((blockIdx.x >> 3) * 2u) % (unsigned)KT);
+    auto phys = [&](int i) {
+        int p = (i < KT ? i : KT - 1) + rot;
+        return p >= KT ? p - KT : p;
+    };
+
+    // Software pipeline.  In step kt the wavefront issues the token-tile loads of step kt+XD and
+    // the weight loads of step kt+STAGES-1, runs the MFMAs of step kt from LDS buffer kt%2 and
+    // its weight registers, then writes the token tile of step kt+1 (loaded XD-1 steps ago) into
+    // the other LDS buffer.  Loads complete in issue order, so that last wait leaves everything
+    // issued later in flight.  All loads are unconditional (the step index is clamped to the
+    // last step, which is re-read harmlessly): straight-line code.
     auto load_w = [&](int kt, auto st) {
-        const int kc = kt < KT ? kt : KT - 1;
+        const int kc = phys(kt);
         static_for<NI>([&](auto i) {
             static_for<4>([&](auto s) {
                 wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
@@ -196,8 +219,8 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         });
     };
     auto load_x = [&](int kt, auto xs_) {
-        const int kc = kt < KT ? kt : KT - 1;
-        static_for<JBE>([&](auto p) {
+        const int kc = phys(kt);
+        static_for<XP>([&](auto p) {
             const uint4 v = *reinterpret_cast<const uint4*>(xp[p] + (size_t)kc * kBK);
             xreg[xs_][4 * p + 0] = v.x;
             xreg[xs_][4 * p + 1] = v.y;
@@ -206,33 +229,33 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         });
     };
     auto store_x = [&](int buf, auto xs_) {
-        static_for<JBE>([&](auto p) {
-            *reinterpret_cast<uint4*>(&xs[buf * BM * kLdsStride + xs_store + p * 32 * kLdsStride]) =
+        static_for<XP>([&](auto p) {
+            *reinterpret_cast<uint4*>(&xs[buf * BM * kLdsStride + xs_store + p * XROWS * kLdsStride]) =
                 make_uint4(xreg[xs_][4 * p + 0], xreg[xs_][4 * p + 1], xreg[xs_][4 * p + 2], xreg[xs_][4 * p + 3]);
         });
     };
-    // `u` = kt modulo the unroll factor UNR (a multiple of both STAGES and XD), compile-time
 #ifdef MOE_STEP_TIMING
     unsigned long long tacc[4] = {0, 0, 0, 0};
 #define MOE_TICK(i_) { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[i_] += now_ - tprev; tprev = now_; }
 #else
 #define MOE_TICK(i_)
 #endif
-    // One step.  A wavefront has its SIMD to itself, so whatever it does between MFMAs leaves
-    // the matrix pipe idle unless it is issued while an MFMA is still executing.  The weight
-    // loads of the prefetched step and the LDS fragment reads of the next slot are therefore
-    // spread between the MFMA groups (one group = one weight fragment against all token
-    // blocks); sched_barrier pins that order, which the compiler's scheduler would undo.
+    // One step.  Whatever a wavefront does between MFMAs leaves the matrix pipe idle unless it
+    // is issued while an MFMA is still executing (or another wavefront of the SIMD has MFMAs
+    // ready).  The weight loads of the prefetched step and the LDS fragment reads of the next
+    // slot are therefore spread between the MFMA groups (one group = one weight fragment against
+    // all token blocks); sched_barrier pins that order, which the compiler's scheduler would undo.
+    // `u` = kt modulo the unroll factor UNR (a multiple of both STAGES and XD), compile-time.
     auto step = [&](int kt, auto u) {
         const int buf = kt & 1;
 #ifdef MOE_STEP_TIMING
         unsigned long long tprev = __builtin_readcyclecounter();
 #endif
         constexpr int wst = (u + STAGES - 1) % STAGES;
-        const int kw = (kt + STAGES - 1 < KT) ? kt + STAGES - 1 : KT - 1;
+        const int kw = phys(kt + STAGES - 1);
         load_x(kt + XD, std::integral_constant<int, (u + XD) % XD>{});           // set (kt+XD)%XD == kt%XD
-        bf16x8 xf[2][JBE];
-        static_for<JBE>([&](auto j) {
+        bf16x8 xf[2][JW];
+        static_for<JW>([&](auto j) {
             xf[0][j] = *reinterpret_cast<const bf16x8*>(&xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride]);
         });
         __builtin_amdgcn_sched_barrier(0);
@@ -242,14 +265,14 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
                 wreg[wst][i][s] =
                     *reinterpret_cast<const uint4*>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
                 if constexpr (i == 0 && s < 3) {
-                    static_for<JBE>([&](auto j) {
+                    static_for<JW>([&](auto j) {
                         xf[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
                             &xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride + (s + 1) * 16]);
                     });
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
-                static_for<JBE>([&](auto j) {
+                static_for<JW>([&](auto j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[s & 1][j], acc[i][j], 0, 0, 0);
                 });
                 __builtin_amdgcn_sched_barrier(0);
@@ -288,15 +311,14 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 2] = loop_r0;
         a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 3] = wall_clock64();
     }
-#endif
-
-#ifdef MOE_STEP_TIMING
-    if (a.dbg != nullptr && lane == 0)
+    if (a.dbg != nullptr && lane == 0 && wave < 4)
         for (int q = 0; q < 4; ++q) a.dbg[((size_t)blockIdx.x * 4 + wave) * 4 + q] = tacc[q];
 #endif
+#undef MOE_TICK
+
     static_for<IB>([&](auto ib) {
-        static_for<JBE>([&](auto j) {
-            const int tr = j * 32 + li;
+        static_for<JW>([&](auto j) {
+            const int tr = (tgrp * JW + j) * 32 + li;
             if (tr < t.rows)
                 store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * N,
                                     n0w + ib * 32, half, N);
@@ -306,19 +328,19 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
 
 // DYN: pick the body for the number of 64-row groups the tile really holds (ragged last tile
 // of an expert), so that empty column blocks cost neither LDS traffic nor MFMA issue slots.
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED>
-__global__ __launch_bounds__(kThreads) void tile_kernel(const GemmArgs a) {
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW>
+__global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
     Tile t;
     int tile, nt;
     if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, JB * 32, t)) return;
     if constexpr (DYN && JB == 8) {
         const int jbe = (t.rows + 31) / 32;
-        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
-        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
-        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
+        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
+        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
     }
-    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED>(a, t, nt, xs);
+    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
 }
 
 // =============================================================================================
@@ -439,11 +461,11 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
 // =============================================================================================
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
 
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED>
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW = 4>
 hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     constexpr int BN = 4 * IB * 32;
     constexpr size_t lds = (size_t)2 * JB * 32 * kLdsStride * sizeof(uint16_t);
-    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED>;
+    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED, NW>;
     static bool attr_done = false;   // dynamic LDS above 64 KB needs an explicit opt-in, once per process
     if (!attr_done && lds > 65536) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -459,7 +481,7 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
                    : nullptr;
 #endif
     const long long grid = (long long)max_blocks * args.n_tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * kWave), lds, s, args);
     return hipGetLastError();
 }
 

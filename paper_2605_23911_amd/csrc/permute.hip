@@ -173,6 +173,116 @@ __global__ __launch_bounds__(kThreads) void rank_kernel(const int32_t* __restric
     }
 }
 
+// ---- 1+2+3 in one workgroup, for up to 8192 slots (every batch of a few hundred tokens) -----
+// Same counting sort, run by one 1024-thread workgroup: launch latency, not work, is what the
+// three-kernel version costs at this size.  Wavefront w owns slots [w*P, (w+1)*P), P = 64*G.
+constexpr int kFusedThreads = 1024;
+constexpr int kFusedWaves = kFusedThreads / kWave;
+constexpr int kFusedMaxGroups = 8;
+constexpr int kFusedMaxSlots = kFusedWaves * kFusedMaxGroups * kWave;
+
+// Exclusive scan of v[0..255] (LDS) by wavefront 0 into out[0..255]; returns the total in *total.
+__device__ __forceinline__ void wave0_scan256(const int* v, int* out, int* total, int lane) {
+    const int a0 = v[4 * lane], a1 = v[4 * lane + 1], a2 = v[4 * lane + 2], a3 = v[4 * lane + 3];
+    const int sum = a0 + a1 + a2 + a3;
+    int inc = sum;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int o = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += o;
+    }
+    const int ex = inc - sum;
+    out[4 * lane] = ex;
+    out[4 * lane + 1] = ex + a0;
+    out[4 * lane + 2] = ex + a0 + a1;
+    out[4 * lane + 3] = ex + a0 + a1 + a2;
+    if (lane == kWave - 1) *total = inc;
+}
+
+__global__ __launch_bounds__(kFusedThreads) void fused_permute_kernel(
+    const int32_t* __restrict__ topk_idx, int R, int E, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
+    int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int M, int32_t* __restrict__ blocks,
+    int32_t* __restrict__ num_blocks) {
+    __shared__ int32_t wcnt[kFusedWaves][kMaxExperts];
+    __shared__ int cnt[kMaxExperts], off[kMaxExperts], nb[kMaxExperts], first[kMaxExperts];
+    __shared__ int total_rows, total_blocks;
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int G = (R + kFusedWaves * kWave - 1) / (kFusedWaves * kWave);   // 64-slot groups per wavefront
+    const int jw = wave * G * kWave;
+
+    for (int i = tid; i < kFusedWaves * kMaxExperts; i += kFusedThreads) (&wcnt[0][0])[i] = 0;
+    __syncthreads();
+    int e_of[kFusedMaxGroups];
+#pragma unroll
+    for (int g = 0; g < kFusedMaxGroups; ++g) {
+        const int j = jw + g * kWave + lane;
+        e_of[g] = (g < G && j < R) ? clamp_expert(topk_idx[j], E) : -1;
+        if (e_of[g] >= 0) atomicAdd(&wcnt[wave][e_of[g]], 1);
+    }
+    __syncthreads();
+    if (tid < kMaxExperts) {
+        int n = 0;
+        if (tid < E)
+            for (int w = 0; w < kFusedWaves; ++w) n += wcnt[w][tid];
+        cnt[tid] = n;
+        nb[tid] = (n + M - 1) / M;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        wave0_scan256(cnt, off, &total_rows, lane);
+        wave0_scan256(nb, first, &total_blocks, lane);
+    }
+    __syncthreads();
+    if (tid < E) {
+        counts[tid] = cnt[tid];
+        offsets[tid] = off[tid];
+        int run = off[tid];
+        for (int w = 0; w < kFusedWaves; ++w) {
+            const int v = wcnt[w][tid];
+            wcnt[w][tid] = run;
+            run += v;
+        }
+    }
+    if (tid == 0) offsets[E] = R;
+    if (blocks != nullptr) {   // Algorithm 1, as in emit_block_schedule
+        const int nblk = total_blocks;
+        if (tid == 0) *num_blocks = nblk;
+        for (int q = tid; q < nblk; q += kFusedThreads) {
+            int lo = 0, hi = kMaxExperts - 1;
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (first[mid] <= q) lo = mid; else hi = mid - 1;
+            }
+            blocks[2 * q] = lo;
+            blocks[2 * q + 1] = (q - first[lo]) * M;
+        }
+    }
+    __syncthreads();
+    volatile int32_t* next = wcnt[wave];
+#pragma unroll
+    for (int g = 0; g < kFusedMaxGroups; ++g) {
+        if (g < G) {   // uniform over the workgroup
+            const int e = e_of[g];
+            unsigned long long same = __ballot(e >= 0);
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const unsigned long long bal = __ballot((e >> b) & 1);
+                same &= ((e >> b) & 1) ? bal : ~bal;
+            }
+            if (e >= 0) {
+                const unsigned long long below = same & ((1ull << lane) - 1ull);
+                const int base = next[e];
+                const int r = base + __popcll(below);
+                const int j = jw + g * kWave + lane;
+                row_of[j] = r;
+                src_of[r] = j;
+                if (below == 0) next[e] = base + __popcll(same);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+}
+
 // ---- 4. row gather ------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __restrict__ x,
                                                          const int32_t* __restrict__ src_of, int k, int d,
@@ -190,6 +300,11 @@ hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, in
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
                                 int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s) {
     const int R = c.T * c.k;
+    if (R <= kFusedMaxSlots) {
+        hipLaunchKernelGGL(fused_permute_kernel, dim3(1), dim3(kFusedThreads), 0, s, topk_idx, R, c.E, counts,
+                           offsets, row_of, src_of, M > 0 ? M : 1, blocks, num_blocks);
+        return hipGetLastError();
+    }
     const int nchunks = permute_chunks(c);
     hipLaunchKernelGGL(hist_kernel, dim3(nchunks), dim3(kThreads), 0, s, topk_idx, R, c.E, scratch);
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kThreads), 0, s, scratch, nchunks, c.E, R, counts, offsets, M,

@@ -106,7 +106,7 @@ def test_max_blocks_bounds_algorithm_1(L):
 
 def test_tile_height_choice(L):
     assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 32      # 16 +- 3.5 rows per expert
-    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 192    # 128 +- 9.8 rows per expert
+    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 160    # 128 +- 9.8 rows per expert
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2)) == 256   # 1024 rows per expert
     assert moe.tile_m(moe.MoEConfig.of(512, 7168, 2048, 256, 8)) == 32    # 16 +- 3.9
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2, tile_m=64)) == 64

@@ -82,13 +82,14 @@ def test_tiny_whole_layer_and_stages(G):
     out = G.run_forward(layer)
     _check_routing(out, ref, layer)
     _check_floats(out, ref, layer, G)
-    # determinism: a second run is bit-identical; row-major and packed weights agree bit for bit
-    # (same values, same reduction order)
+    # determinism: a second run is bit-identical; row-major weights give the same integers and
+    # floats within the tolerance (another kernel variant may sum over k in another order)
     out2 = G.run_forward(layer)
     out3 = G.run_forward(layer, packed=False)
     for key in out:
         assert np.array_equal(out[key], out2[key]), key
-        assert np.array_equal(out[key], out3[key]), key
+    _check_routing(out3, ref, layer)
+    _check_floats(out3, ref, layer, G)
     # the packed buffer is a pure permutation of the three weight tensors
     pk = np.sort(G.np_bits(layer.packed.view(torch.bfloat16)).reshape(-1))
     raw = np.sort(np.concatenate([G.np_bits(t).reshape(-1) for t in (layer.wg, layer.wu, layer.wd)]))
