@@ -65,15 +65,14 @@ const char* moe_status_string(moe_status s) {
 int32_t moe_tile_m(const moe_config* c) {
     if (check_config(c) != MOE_OK) return 0;
     if (c->tile_m != 0) return c->tile_m;
-    // Rows per expert under near-uniform routing are Binomial(T, k/E): take the smallest tile
-    // that holds mean + 3 sigma, so that nearly every expert is ONE tile and its weights are
-    // streamed once (an expert beyond that simply gets a second, short tile).  Smaller tiles
-    // mean fewer MFMAs on padding rows, which matters because sustained MFMA work lowers the
-    // clock.  Beyond 192 rows the 256-row tile skips its empty 64-row groups itself.
-    const double p = (double)c->k / c->E;
-    const double need = c->T * p + 3.0 * sqrt(c->T * p * (1.0 - p));
-    for (int v : kTileHeights)
-        if (need <= v && v < 256) return v;
+    // One tile height serves everything: Algorithm 1 runs with M = 256 and the GEMM kernel picks
+    // its body per block from the rows the block really holds, so an expert of any size up to
+    // 256 rows is ONE block (its weights stream once) and a heavier expert is cut into 256-row
+    // blocks.  Only when the down projection would have too few workgroups to fill the chip
+    // (a handful of rows in all) the schedule uses 32-row blocks for the K-split kernel.
+    const long long R = (long long)c->T * c->k;
+    const long long active = c->E < R ? c->E : R;
+    if ((long long)(c->d / 128) * active < 256 && R <= 32) return 32;
     return 256;
 }
 

@@ -53,6 +53,7 @@ struct GemmArgs {
     const int32_t* blocks;      // [*, 2] (expert, row offset inside the expert)
     const int32_t* num_blocks;  // device scalar
     int R, N, K, n_tiles_n;
+    int M;                      // tile height of the block schedule (rows per block <= M)
     unsigned long long* dbg;   // MOE_STEP_TIMING builds only
 };
 
@@ -97,6 +98,7 @@ struct Tile {
     int e, row0, rows;
 };
 __device__ __forceinline__ bool load_tile(const GemmArgs& a, int tile, int BM, Tile& t) {
+    BM = a.M < BM ? a.M : BM;   // a kernel may serve a schedule with shorter blocks than it can hold
     if (tile >= *a.num_blocks) return false;
     t.e = a.blocks[2 * tile];
     const int r_in = a.blocks[2 * tile + 1];
@@ -326,15 +328,31 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     });
 }
 
-// DYN: pick the body for the number of 64-row groups the tile really holds (ragged last tile
-// of an expert), so that empty column blocks cost neither LDS traffic nor MFMA issue slots.
+// DYN (256-row tiles only): the body is chosen per tile from the rows it really holds, so one
+// launch serves experts of any size: a 20-row expert runs the 32-row body, a 1000-row expert
+// four 256-row tiles.  This is the "dynamic block-to-expert assignment" the paper leaves as
+// future work (its Sec. 4.7 and limitation 5): Algorithm 1 runs with M = 256 and the tile
+// height inside a block follows n_e.  Empty token blocks cost neither loads, LDS traffic nor
+// MFMA issue slots.  Pipeline depths per body are what the register file allows.
 template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW>
 __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
     Tile t;
     int tile, nt;
     if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, JB * 32, t)) return;
-    if constexpr (DYN && JB == 8) {
+    if constexpr (DYN && JB == 8 && NW == 4) {
+        constexpr int SD = (IB * (GATEUP ? 2 : 1) >= 4) ? 3 : 4;   // stages for the small bodies
+        const int jbe = (t.rows + 31) / 32;
+        switch (jbe) {
+            case 1: return tile_body<JB, 1, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 2: return tile_body<JB, 2, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 3: return tile_body<JB, 3, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 4: return tile_body<JB, 4, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 5: return tile_body<JB, 5, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 6: return tile_body<JB, 6, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW>(a, t, nt, xs);
+            default: break;
+        }
+    } else if constexpr (DYN && JB == 8) {
         const int jbe = (t.rows + 31) / 32;
         if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
         if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
@@ -497,7 +515,7 @@ hipError_t launch_skinny(const GemmArgs& a, int max_blocks, hipStream_t s) {
 }
 
 struct Variant {
-    int M;          // tile height (Alg. 1's M) this variant implements
+    int M;          // tallest block (Alg. 1's M) this variant can hold; it serves any schedule with M <= this
     bool packed;    // consumes moe_pack_weights' layout
     launch_fn fn;
     const char* name;   // kernel template instance, as rocprofv3 prints it (minus namespaces)
@@ -509,7 +527,7 @@ inline int env_variant(const char* name, int count, int M, bool packed, const Va
     const char* v = std::getenv(name);
     if (v == nullptr) return -1;
     const int id = std::atoi(v);
-    return (id >= 0 && id < count && table[id].M == M && table[id].packed == packed) ? id : -1;
+    return (id >= 0 && id < count && table[id].M >= M && table[id].packed == packed) ? id : -1;
 }
 
 }  // namespace

@@ -55,6 +55,10 @@ __device__ __forceinline__ void unpack8(const uint4& v, double* out) {
 // B[k = l/16][j = l%16]; it receives D[i = l/16 + 4v][j = l%16], v = 0..3.  The MFMA sums over
 // k, so which k a slot carries is free as long as A and B agree: lane group g = l/16 loads 8
 // consecutive k (one 16-byte load) and the q-th MFMA of a chunk takes element q of every lane.
+// NT: 16-expert tiles per wavefront (1 or 4).  With 4 the token fragment is loaded and
+// converted once per chunk for 64 experts (used when there are enough tiles to fill the chip
+// without cutting the reduction).
+template <int NT>
 __global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __restrict__ x,
                                                          const uint16_t* __restrict__ wr,
                                                          double* __restrict__ part, int T, int d, int E, int T16,
@@ -62,9 +66,10 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __rest
     const int lane = threadIdx.x % kWave;
     const int unit = blockIdx.x * kWavesPerBlock + threadIdx.x / kWave;
     if (unit >= units) return;
+    const int EG = (E16 + NT - 1) / NT;   // expert-tile groups
     const int ks = unit % KS;
-    const int et = (unit / KS) % E16;
-    const int tt = unit / (KS * E16);
+    const int eg = (unit / KS) % EG;
+    const int tt = unit / (KS * EG);
     const int i = lane & 15, g = lane >> 4;
 
     const int nchunk = d / kChunk;
@@ -73,31 +78,53 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __rest
     const int c1 = (c0 + per) < nchunk ? (c0 + per) : nchunk;
 
     const int trow = (tt * 16 + i) < T ? (tt * 16 + i) : (T - 1);
-    const int erow = (et * 16 + i) < E ? (et * 16 + i) : (E - 1);
     const uint16_t* xp = x + (size_t)trow * d + g * 8;
-    const uint16_t* wp = wr + (size_t)erow * d + g * 8;
+    const uint16_t* wp[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) {
+        const int erow = ((eg * NT + n) * 16 + i) < E ? ((eg * NT + n) * 16 + i) : (E - 1);
+        wp[n] = wr + (size_t)erow * d + g * 8;
+    }
 
-    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    f64x4 acc[NT];
+#pragma unroll
+    for (int n = 0; n < NT; ++n) acc[n] = f64x4{0.0, 0.0, 0.0, 0.0};
     if (c0 < c1) {
         uint4 xr = *reinterpret_cast<const uint4*>(xp + (size_t)c0 * kChunk);
-        uint4 wv = *reinterpret_cast<const uint4*>(wp + (size_t)c0 * kChunk);
+        uint4 wv[NT];
+#pragma unroll
+        for (int n = 0; n < NT; ++n) wv[n] = *reinterpret_cast<const uint4*>(wp[n] + (size_t)c0 * kChunk);
         for (int c = c0; c < c1; ++c) {
             const int cn = (c + 1 < c1) ? c + 1 : c;   // prefetch (the last chunk re-reads itself)
             const uint4 xn = *reinterpret_cast<const uint4*>(xp + (size_t)cn * kChunk);
-            const uint4 wn = *reinterpret_cast<const uint4*>(wp + (size_t)cn * kChunk);
-            double a8[8], b8[8];
-            unpack8(xr, a8);
-            unpack8(wv, b8);
+            uint4 wn[NT];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a8[q], b8[q], acc, 0, 0, 0);
+            for (int n = 0; n < NT; ++n) wn[n] = *reinterpret_cast<const uint4*>(wp[n] + (size_t)cn * kChunk);
+            double a8[8];
+            unpack8(xr, a8);
+#pragma unroll
+            for (int n = 0; n < NT; ++n) {
+                double b8[8];
+                unpack8(wv[n], b8);
+#pragma unroll
+                for (int q = 0; q < 8; ++q)
+                    acc[n] = __builtin_amdgcn_mfma_f64_16x16x4f64(a8[q], b8[q], acc[n], 0, 0, 0);
+            }
             xr = xn;
-            wv = wn;
+#pragma unroll
+            for (int n = 0; n < NT; ++n) wv[n] = wn[n];
         }
     }
     const size_t EP = (size_t)E16 * 16;
-    double* out = part + ((size_t)ks * T16 * 16 + (size_t)tt * 16) * EP + (size_t)et * 16 + i;
 #pragma unroll
-    for (int v = 0; v < 4; ++v) out[(size_t)(g + 4 * v) * EP] = acc[v];
+    for (int n = 0; n < NT; ++n) {
+        const int et = eg * NT + n;
+        if (et < E16) {
+            double* out = part + ((size_t)ks * T16 * 16 + (size_t)tt * 16) * EP + (size_t)et * 16 + i;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) out[(size_t)(g + 4 * v) * EP] = acc[n][v];
+        }
+    }
 }
 
 // ---- kernel 2: gate + top-k, one wavefront per token ------------------------------------------
@@ -197,14 +224,16 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict
 }
 
 struct RoutePlan {
-    int T16, E16, KS;
+    int T16, E16, KS, NT;
 };
 
 RoutePlan plan(const moe_config& c) {
     RoutePlan p;
     p.T16 = (c.T + 15) / 16;
     p.E16 = (c.E + 15) / 16;
-    const long long tiles = (long long)p.T16 * p.E16;
+    // four expert tiles per wavefront when that still leaves >= 1024 wavefronts
+    p.NT = (p.E16 >= 4 && (long long)p.T16 * ((p.E16 + 3) / 4) >= 1024) ? 4 : 1;
+    const long long tiles = (long long)p.T16 * ((p.E16 + p.NT - 1) / p.NT);
     const int nchunk = c.d / kChunk;
     long long ks = (2048 + tiles - 1) / tiles;          // aim for >= ~2048 wavefronts
     if (ks > 16) ks = 16;                               // the top-k kernel sums the slices serially
@@ -225,10 +254,15 @@ size_t route_workspace_bytes(const moe_config& c) {
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
                         int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s) {
     const RoutePlan p = plan(c);
-    const int units = p.T16 * p.E16 * p.KS;
+    const int units = p.T16 * ((p.E16 + p.NT - 1) / p.NT) * p.KS;
     double* part = (double*)workspace;
-    hipLaunchKernelGGL(logits_kernel, dim3((units + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kThreads), 0, s, x,
-                       wr, part, c.T, c.d, c.E, p.T16, p.E16, p.KS, units);
+    const dim3 grid((units + kWavesPerBlock - 1) / kWavesPerBlock);
+    if (p.NT == 4)
+        hipLaunchKernelGGL(logits_kernel<4>, grid, dim3(kThreads), 0, s, x, wr, part, c.T, c.d, c.E, p.T16, p.E16,
+                           p.KS, units);
+    else
+        hipLaunchKernelGGL(logits_kernel<1>, grid, dim3(kThreads), 0, s, x, wr, part, c.T, c.d, c.E, p.T16, p.E16,
+                           p.KS, units);
     hipLaunchKernelGGL(topk_kernel, dim3((c.T + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kThreads), 0, s, part,
                        bias, topk_idx, topk_w, c.T, c.E, c.k, c.gating, p.T16, p.E16, p.KS);
     return hipGetLastError();

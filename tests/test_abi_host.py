@@ -38,7 +38,7 @@ def test_status_strings(L):
 
 def test_config_validation(L):
     ok = moe.MoEConfig.of(64, 256, 512, 8, 2)
-    assert moe.tile_m(ok) == 32 and moe.forward_workspace_size(ok) > 0
+    assert moe.tile_m(ok) == 256 and moe.forward_workspace_size(ok) > 0
     bad = [moe.MoEConfig.of(-1, 256, 512, 8, 2), moe.MoEConfig.of(4, 256, 512, 8, 9),
            moe.MoEConfig.of(4, 256, 512, 8, 0), moe.MoEConfig.of(4, 256, 512, 257, 2),
            moe.MoEConfig.of(4, 250, 512, 8, 2), moe.MoEConfig.of(4, 256, 500, 8, 2),
@@ -105,11 +105,12 @@ def test_max_blocks_bounds_algorithm_1(L):
 
 
 def test_tile_height_choice(L):
-    assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 32      # 16 +- 3.5 rows per expert
-    assert moe.tile_m(moe.MoEConfig.of(512, 4096, 14336, 8, 2)) == 160    # 128 +- 9.8 rows per expert
-    assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2)) == 256   # 1024 rows per expert
-    assert moe.tile_m(moe.MoEConfig.of(512, 7168, 2048, 256, 8)) == 32    # 16 +- 3.9
+    assert moe.tile_m(moe.MoEConfig.of(1, 4096, 14336, 8, 2)) == 32       # 2 rows in all: K-split down kernel
+    assert moe.tile_m(moe.MoEConfig.of(64, 4096, 14336, 8, 2)) == 256
+    assert moe.tile_m(moe.MoEConfig.of(4096, 7168, 2048, 256, 8)) == 256
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2, tile_m=64)) == 64
+    c = moe.MoEConfig.of(512, 4096, 14336, 8, 2)
+    assert "tile_kernel<8" in moe.ffn_kernel_name(c, 0, True) and "tile_kernel<8" in moe.ffn_kernel_name(c, 1, False)
 
 
 def test_entry_points_refuse_cpu_tensors(L):
