@@ -16,6 +16,8 @@ const Variant kDown[] = {
     /*7*/ {32, true, launch_skinny<1, false, 4, 1, true>, "skinny_kernel<1, false, 4, 1, true>"},
     /*8*/ {32, true, launch_tile<1, 1, false, 6, 3, false, true>, "tile_kernel<1, 1, false, 6, 3, false, true, 4>"},
     /*9*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 8>, "tile_kernel<8, 2, false, 2, 1, true, true, 8>"},
+    /*10*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
+    /*11*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 

@@ -17,6 +17,7 @@ const Variant kGateUp[] = {
     /*6*/ {32, true, launch_tile<1, 1, true, 4, 2, false, true>, "tile_kernel<1, 1, true, 4, 2, false, true, 4>"},
     /*7*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 8>, "tile_kernel<8, 1, true, 2, 1, true, true, 8>"},
     /*8*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>, "tile_kernel<4, 2, true, 2, 1, false, true, 4>"},
+    /*9*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 

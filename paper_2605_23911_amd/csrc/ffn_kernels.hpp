@@ -328,6 +328,154 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     });
 }
 
+// ---------------------------------------------------------------------------------------------
+// tile_body_dma: same tile, but the token tile goes global -> LDS with the gfx950 LDS-DMA load
+// (global_load_lds_dwordx4: each lane supplies its own global address, the 64 x 16 bytes land
+// contiguously at M0 + 16*lane), so it needs no staging registers, no ds_write, and can be
+// prefetched XD steps ahead into a ring of XD+1 LDS buffers.  LDS rows are 128 bytes, unpadded
+// (the DMA fixes the destination order); bank conflicts are avoided by permuting the SOURCE:
+// position p of row r holds chunk p ^ swz(r), swz(r) = (r ^ (r >> 3)) & 7, and the fragment
+// reads apply the same XOR.  The DMA is issued from inline assembly so that the compiler does
+// not serialise every later LDS read behind it; completion is awaited with an explicit
+// s_waitcnt vmcnt(N) before the step's barrier (loads complete in issue order; N = the number
+// of vector-memory loads this wavefront issues after the batch it waits for).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr) {
+    const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr);   // wave-uniform: goes through M0
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(base)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
+    // gfx9 encoding: vmcnt[3:0] -> bits 3:0, vmcnt[5:4] -> bits 15:14; expcnt (6:4) and lgkmcnt (11:8) = no wait
+    __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED>
+__device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
+    constexpr int NM = GATEUP ? 2 : 1;
+    constexpr int NI = IB * NM;
+    constexpr int BN = 4 * IB * 32;
+    constexpr int NBUF = XD + 1;
+    constexpr int BUF_BYTES = JBE * 32 * 128;
+    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int li = lane & 31, half = lane >> 5;
+    const int K = a.K, N = a.N;
+    const int KT = K / kBK;
+    const int n0w = nt * BN + wave * (IB * 32);
+
+    typedef WAddr<PACKED, NM> WA;
+    const uint16_t* wp[NI];
+    static_for<NM>([&](auto m) {
+        static_for<IB>([&](auto ib) { wp[m * IB + ib] = WA::base(a, t.e, n0w / 32 + ib, m, lane); });
+    });
+    // DMA q of this wavefront covers the 8 rows rg*8.., rg = 4q + wave: lane -> row rg*8 + lane/8,
+    // LDS position lane%8, source chunk position ^ swz(row) with swz = ((lane>>3) ^ rg) & 7.
+    const uint16_t* xp[JBE];
+    static_for<JBE>([&](auto q) {
+        const int rg = q * 4 + wave;
+        int row = t.row0 + rg * 8 + (lane >> 3);
+        row = row < a.R ? row : a.R - 1;
+        const int chunk = (lane & 7) ^ (((lane >> 3) ^ rg) & 7);
+        xp[q] = a.X + (size_t)row * K + chunk * 8;
+    });
+    const uint32_t lds0 = (uint32_t)(uintptr_t)xs;            // LDS byte address of the ring
+    const uint32_t dma_dst = lds0 + wave * 1024;              // + q*4096 + buffer*BUF_BYTES
+    // fragment reads: row j*32 + li, logical chunk 2s + half, swizzle (li ^ li>>3 ^ 4(j&1)) & 7
+    const int sw0 = (li ^ (li >> 3)) & 7;
+    int rd_off[2][4];   // [j parity][slot] byte offset inside a row
+    static_for<2>([&](auto pj) {
+        static_for<4>([&](auto s) { rd_off[pj][s] = (((2 * s + half) ^ (sw0 ^ (pj * 4))) & 7) * 16; });
+    });
+    const char* xs_b = reinterpret_cast<const char*>(xs) + li * 128;
+
+    f32x16 acc[NI][JBE];
+    static_for<NI>([&](auto i) {
+        static_for<JBE>([&](auto j) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        });
+    });
+    uint4 wreg[STAGES][NI][4];
+
+    const int rot = (int)(((blockIdx.x >> 3) * 2u) % (unsigned)KT);   // see tile_body
+    auto phys = [&](int i) {
+        int p = (i < KT ? i : KT - 1) + rot;
+        return p >= KT ? p - KT : p;
+    };
+    auto load_w = [&](int kt, auto st) {
+        const int kc = phys(kt);
+        static_for<NI>([&](auto i) {
+            static_for<4>([&](auto s) {
+                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+            });
+        });
+    };
+    auto dma_x = [&](int kt, int buf) {
+        const int kc = phys(kt);
+        static_for<JBE>([&](auto q) { lds_dma16(xp[q] + (size_t)kc * kBK, dma_dst + buf * BUF_BYTES + q * 4096); });
+    };
+    auto frag = [&](int buf, auto j, auto s) {
+        return *reinterpret_cast<const bf16x8*>(xs_b + buf * BUF_BYTES + j * 4096 + rd_off[j & 1][s]);
+    };
+    // loads this wavefront issues after the DMA batch of step kt+1-XD and before the end of
+    // step kt: that step's weight prefetch, then (XD-1) steps of DMA + weight prefetch
+    constexpr int VM_AFTER = NI * 4 + (XD - 1) * (JBE + NI * 4);
+
+    auto step = [&](int kt, auto u) {
+        const int buf = kt % NBUF;
+        constexpr int wst = (u + STAGES - 1) % STAGES;
+        const int kw = phys(kt + STAGES - 1);
+        dma_x(kt + XD, (kt + XD) % NBUF);   // the buffer read in step kt-1: free since that step's barrier
+        bf16x8 xf[2][JBE];
+        static_for<JBE>([&](auto j) { xf[0][j] = frag(buf, j, std::integral_constant<int, 0>{}); });
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<4>([&](auto s) {
+            static_for<NI>([&](auto i) {
+                wreg[wst][i][s] =
+                    *reinterpret_cast<const uint4*>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                if constexpr (i == 0 && s < 3) {
+                    static_for<JBE>([&](auto j) {
+                        xf[(s + 1) & 1][j] = frag(buf, j, std::integral_constant<int, s + 1>{});
+                    });
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
+                static_for<JBE>([&](auto j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[s & 1][j], acc[i][j], 0, 0, 0);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+        wait_vmcnt<VM_AFTER>();   // this wavefront's share of the token tile of step kt+1 has landed
+        __syncthreads();
+    };
+
+    // prologue: token tiles of steps 0..XD-1, weights of steps 0..STAGES-2; step 0 must be complete
+    static_for<XD>([&](auto q) { dma_x(q, q % NBUF); });
+    static_for<STAGES - 1>([&](auto st) { load_w(st, st); });
+    wait_vmcnt<(XD - 1) * JBE + (STAGES - 1) * NI * 4>();
+    __syncthreads();
+
+    constexpr int UNR = STAGES;
+    int kt = 0;
+    for (; kt + UNR <= KT; kt += UNR) static_for<UNR>([&](auto u) { step(kt + u, u); });
+    static_for<UNR>([&](auto u) {
+        if (kt + u < KT) step(kt + u, u);
+    });
+    wait_vmcnt<0>();   // nothing of this workgroup may still be writing LDS when it retires
+
+    static_for<IB>([&](auto ib) {
+        static_for<JBE>([&](auto j) {
+            const int tr = j * 32 + li;
+            if (tr < t.rows)
+                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * N,
+                                    n0w + ib * 32, half, N);
+        });
+    });
+}
+
 // DYN (256-row tiles only): the body is chosen per tile from the rows it really holds, so one
 // launch serves experts of any size: a 20-row expert runs the 32-row body, a 1000-row expert
 // four 256-row tiles.  This is the "dynamic block-to-expert assignment" the paper leaves as
@@ -359,6 +507,26 @@ __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
         if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
     }
     tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
+}
+
+// The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
+template <int IB, bool GATEUP, bool PACKED>
+__global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
+    Tile t;
+    int tile, nt;
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
+    constexpr int NI = IB * (GATEUP ? 2 : 1);
+    constexpr int SD = NI >= 4 ? 3 : 4;
+    switch ((t.rows + 31) / 32) {
+        case 1: return tile_body_dma<8, 1, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
+        case 2: return tile_body_dma<8, 2, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
+        case 3: return tile_body_dma<8, 3, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
+        case 4: return tile_body_dma<8, 4, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
+        case 5: return tile_body_dma<8, 5, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
+        case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
+        default: return tile_body_dma<8, 8, IB, GATEUP, NI >= 2 ? 2 : 3, 3, PACKED>(a, t, nt, xs);
+    }
 }
 
 // =============================================================================================
@@ -500,6 +668,22 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
 #endif
     const long long grid = (long long)max_blocks * args.n_tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * kWave), lds, s, args);
+    return hipGetLastError();
+}
+
+template <int IB, bool GATEUP, bool PACKED>
+hipError_t launch_tile_dma(const GemmArgs& a, int max_blocks, hipStream_t s) {
+    constexpr int BN = 4 * IB * 32;
+    constexpr int lds = 4 * 8 * 32 * 128;   // XD+1 = 4 buffers of 256 rows x 128 bytes
+    auto kern = tile_kernel_dma<IB, GATEUP, PACKED>;
+    // once per process and kernel: not allowed while a stream is being captured into a graph
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    GemmArgs args = a;
+    args.n_tiles_n = (a.N + BN - 1) / BN;
+    const long long grid = (long long)max_blocks * args.n_tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
 }
 

@@ -159,6 +159,50 @@ def test_degenerate_shapes(G, T, E, k, packed):
     _check_floats(out, ref, layer, G)
 
 
+def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
+    """The GEMM variants that stage the token tile with LDS-DMA loads (selected by environment
+    variable; not the default) against the oracle, and a HIP-graph capture of moe_forward whose
+    replays must equal the eager result bit for bit (the library enqueues kernels only)."""
+    import paper_2605_23911_amd as moe
+    s = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
+    layer = G.Layer(s, seed=3, skew=2.0)
+    ref = _oracle_full(layer)
+    monkeypatch.setenv("MOE_GU_VARIANT", "9")
+    monkeypatch.setenv("MOE_DN_VARIANT", "10")
+    cfg = layer.cfg()
+    assert "dma" in moe.ffn_kernel_name(cfg, 0, True) and "dma" in moe.ffn_kernel_name(cfg, 1, True)
+    _say("LDS-DMA variants on the ragged shape")
+    out = G.run_forward(layer)
+    _check_routing(out, ref, layer)
+    _check_floats(out, ref, layer, G)
+    monkeypatch.delenv("MOE_GU_VARIANT")
+    monkeypatch.delenv("MOE_DN_VARIANT")
+    _say("graph capture + replays of the default path")
+    lay = moe.forward_workspace_layout(cfg)
+    ws = torch.zeros(lay.total, dtype=torch.uint8, device=G.DEV)
+    y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=G.DEV)
+    run = lambda: moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, None, None, None, y, ws, W_packed=layer.packed)
+    run()
+    torch.cuda.synchronize()
+    y_eager = y.clone()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    for _ in range(3):
+        y.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager)
+        run()                      # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y, y_eager)
+
+
 def test_zero_tokens_is_a_noop(G):
     import paper_2605_23911_amd as moe
     cfg = moe.MoEConfig.of(0, 64, 128, 4, 2)
