@@ -188,7 +188,7 @@ def main():
         "stages_ms": stages,
     }
     if not args.no_cpu_baseline:
-        sample = args.cpu_sample or 256
+        sample = args.cpu_sample or min(s.T, 1024)
         result["cpu_baseline"], ref = cpu_baseline(s, x_cpu, wr_cpu, bias_cpu, args.seed, sample)
         yb = y.cpu().view(torch.int16).numpy().view(np.uint16)[ref["tokens"]]
         yg = (yb.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)

@@ -24,13 +24,14 @@ constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 // few_rows: the projection has too few output rows to give every CU a workgroup (T = 1 on an
 // 8-expert model: 2 experts x 4096 output rows = 64 workgroups of 128 rows), so the skinny
 // kernel splits K over its four wavefronts.  wide: two 32-row weight blocks per wavefront when
-// that still leaves >= 1024 workgroups: the token tile is then re-read from L2 half as often
-// per weight byte (DeepSeek-V3 shape: 2048-long rows, 256 experts).
+// that still leaves >= 512 workgroups: every token fragment read from LDS then feeds twice as
+// many MFMAs and the token tile is re-read from L2 half as often per weight byte (DeepSeek-V3
+// shape: 2048-long rows, 256 experts; any shape once experts hold several 256-row blocks).
 int pick(int M, bool packed, const moe_config& c) {
     const long long R = (long long)c.T * c.k;
     const long long active = c.E < R ? c.E : R;
     const bool few_rows = (long long)(c.d / 128) * active < 256;
-    const bool wide = (long long)(c.d / 256) * active >= 1024;
+    const bool wide = (long long)(c.d / 256) * (active + R / 256) >= 512;
     if (few_rows && M <= 32) return packed ? 5 : 1;
     if (few_rows && M <= 64) return packed ? 6 : 2;
     if (!packed) return 0;
