@@ -18,6 +18,9 @@ const Variant kDown[] = {
     /*9*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 8>, "tile_kernel<8, 2, false, 2, 1, true, true, 8>"},
     /*10*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
     /*11*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
+    /*12*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true, 4, true>, "tile_kernel<8, 1, false, 4, 2, true, true, 4, true>"},
+    /*13*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 4, true>, "tile_kernel<8, 2, false, 2, 1, true, true, 4, true>"},
+    /*14*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false, 4, true>, "tile_kernel<8, 1, false, 3, 1, true, false, 4, true>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -34,7 +37,10 @@ int pick(int M, bool packed, const moe_config& c) {
     const bool wide = (long long)(c.d / 256) * (active + R / 256) >= 512;
     if (few_rows && M <= 32) return packed ? 5 : 1;
     if (few_rows && M <= 64) return packed ? 6 : 2;
-    if (!packed) return 0;
+    // non-temporal weight loads while experts are single blocks and the token buffers are small
+    const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
+    if (!packed) return once ? 14 : 0;
+    if (once) return wide ? 13 : 12;
     return wide ? 4 : 3;
 }
 

@@ -18,18 +18,29 @@ const Variant kGateUp[] = {
     /*7*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 8>, "tile_kernel<8, 1, true, 2, 1, true, true, 8>"},
     /*8*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>, "tile_kernel<4, 2, true, 2, 1, false, true, 4>"},
     /*9*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
+    /*10*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, true, 4, true>"},
+    /*11*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, false, 4, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
 // The dynamic-height 256-row kernel serves every schedule (its body follows the rows each block
 // really holds); the others are kept for comparison runs.
-int pick(int M, bool packed) { return packed ? 3 : 0; }
+// Non-temporal weight loads while every expert is (nearly always) a single block and the token
+// buffer is small enough to live in L2 / Infinity Cache; see load_w16.
+bool stream_once(const moe_config& c) {
+    const double R = (double)c.T * c.k;
+    return R / c.E <= 192.0 && R * c.d * 2.0 <= 128e6;
+}
+int pick(int M, bool packed, const moe_config& c) {
+    if (stream_once(c)) return packed ? 10 : 11;
+    return packed ? 3 : 0;
+}
 
 }  // namespace
 
 const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed) {
     int id = env_variant("MOE_GU_VARIANT", kNumGateUp, M, packed, kGateUp);
-    if (id < 0) id = pick(M, packed);
+    if (id < 0) id = pick(M, packed, c);
     return kGateUp[id].name;
 }
 
@@ -39,7 +50,7 @@ hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm
     GemmArgs a{x_perm, wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
     const bool packed = packed_gu != nullptr;
     int id = env_variant("MOE_GU_VARIANT", kNumGateUp, M, packed, kGateUp);
-    if (id < 0) id = pick(M, packed);
+    if (id < 0) id = pick(M, packed, c);
     if (kGateUp[id].M < M) return hipErrorInvalidValue;
     return kGateUp[id].fn(a, moe_max_blocks(&c, M), s);
 }

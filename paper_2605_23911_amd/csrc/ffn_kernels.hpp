@@ -68,6 +68,21 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
+// Weight loads.  NT: when every expert is a single block each weight byte is used exactly once
+// per launch, and loading it with the non-temporal hint keeps the streamed weights from evicting
+// the re-used token tiles from L2 (+5..10 % at T <= 512).  When an expert spans several row
+// blocks they share the weight panel through L2 and the hint would defeat that.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+template <bool NT>
+__device__ __forceinline__ uint4 load_w16(const uint16_t* p) {
+    if constexpr (NT) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        return make_uint4(v[0], v[1], v[2], v[3]);
+    } else {
+        return *reinterpret_cast<const uint4*>(p);
+    }
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) {
     // SiLU(g) * u with SiLU(g) = g / (1 + exp(-g)); exp(-g) = inf for very negative g gives -0.
     return g * __frcp_rn(1.0f + __expf(-g)) * u;
@@ -149,7 +164,7 @@ __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, ui
 //         accumulators per wavefront -> two wavefronts per SIMD, so one wavefront's load issue,
 //         LDS waits and barrier overlap with the other's MFMAs.
 // =============================================================================================
-template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, int NW>
+template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, int NW, bool WNT>
 __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NM = GATEUP ? 2 : 1;
     constexpr int NI = IB * NM;
@@ -216,7 +231,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         const int kc = phys(kt);
         static_for<NI>([&](auto i) {
             static_for<4>([&](auto s) {
-                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+                wreg[st][i][s] = load_w16<WNT>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
             });
         });
     };
@@ -264,8 +279,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         MOE_TICK(0)
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
-                wreg[wst][i][s] =
-                    *reinterpret_cast<const uint4*>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                wreg[wst][i][s] = load_w16<WNT>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
                 if constexpr (i == 0 && s < 3) {
                     static_for<JW>([&](auto j) {
                         xf[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
@@ -352,7 +366,7 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED>
+template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT = false>
 __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NM = GATEUP ? 2 : 1;
     constexpr int NI = IB * NM;
@@ -408,7 +422,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
         const int kc = phys(kt);
         static_for<NI>([&](auto i) {
             static_for<4>([&](auto s) {
-                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+                wreg[st][i][s] = load_w16<WNT>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
             });
         });
     };
@@ -433,8 +447,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
         __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
-                wreg[wst][i][s] =
-                    *reinterpret_cast<const uint4*>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                wreg[wst][i][s] = load_w16<WNT>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
                 if constexpr (i == 0 && s < 3) {
                     static_for<JBE>([&](auto j) {
                         xf[(s + 1) & 1][j] = frag(buf, j, std::integral_constant<int, s + 1>{});
@@ -482,7 +495,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
 // future work (its Sec. 4.7 and limitation 5): Algorithm 1 runs with M = 256 and the tile
 // height inside a block follows n_e.  Empty token blocks cost neither loads, LDS traffic nor
 // MFMA issue slots.  Pipeline depths per body are what the register file allows.
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW>
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW, bool WNT>
 __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
     Tile t;
@@ -492,21 +505,21 @@ __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
         constexpr int SD = (IB * (GATEUP ? 2 : 1) >= 4) ? 3 : 4;   // stages for the small bodies
         const int jbe = (t.rows + 31) / 32;
         switch (jbe) {
-            case 1: return tile_body<JB, 1, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
-            case 2: return tile_body<JB, 2, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
-            case 3: return tile_body<JB, 3, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
-            case 4: return tile_body<JB, 4, IB, GATEUP, SD, 2, PACKED, NW>(a, t, nt, xs);
-            case 5: return tile_body<JB, 5, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW>(a, t, nt, xs);
-            case 6: return tile_body<JB, 6, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW>(a, t, nt, xs);
+            case 1: return tile_body<JB, 1, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
+            case 2: return tile_body<JB, 2, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
+            case 3: return tile_body<JB, 3, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
+            case 4: return tile_body<JB, 4, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
+            case 5: return tile_body<JB, 5, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
+            case 6: return tile_body<JB, 6, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
             default: break;
         }
     } else if constexpr (DYN && JB == 8) {
         const int jbe = (t.rows + 31) / 32;
-        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
-        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
-        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
+        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
+        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
+        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
     }
-    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED, NW>(a, t, nt, xs);
+    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
 }
 
 // The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
@@ -535,7 +548,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
 // SPLITK == 4: they share one weight block and each reduces a quarter of K; partial sums are
 // added in wavefront order through LDS (fixed order: bit-reproducible).
 // =============================================================================================
-template <int JB, bool GATEUP, int STAGES, int SPLITK, bool PACKED>
+template <int JB, bool GATEUP, int STAGES, int SPLITK, bool PACKED, bool WNT = true>
 __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
     constexpr int NM = GATEUP ? 2 : 1;
     constexpr int BM = JB * 32;
@@ -580,7 +593,7 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
         kc = kc > 0 ? kc : 0;
         static_for<NM>([&](auto i) {
             static_for<4>([&](auto s) {
-                wreg[st][i][s] = *reinterpret_cast<const uint4*>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+                wreg[st][i][s] = load_w16<WNT>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
             });
         });
         static_for<JB>([&](auto j) {
@@ -647,11 +660,11 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
 // =============================================================================================
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
 
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW = 4>
+template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW = 4, bool WNT = false>
 hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     constexpr int BN = 4 * IB * 32;
     constexpr size_t lds = (size_t)2 * JB * 32 * kLdsStride * sizeof(uint16_t);
-    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED, NW>;
+    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED, NW, WNT>;
     static bool attr_done = false;   // dynamic LDS above 64 KB needs an explicit opt-in, once per process
     if (!attr_done && lds > 65536) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
