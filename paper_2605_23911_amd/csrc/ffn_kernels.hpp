@@ -433,17 +433,23 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     auto frag = [&](int buf, auto j, auto s) {
         return *reinterpret_cast<const bf16x8*>(xs_b + buf * BUF_BYTES + j * 4096 + rd_off[j & 1][s]);
     };
-    // loads this wavefront issues after the DMA batch of step kt+1-XD and before the end of
-    // step kt: that step's weight prefetch, then (XD-1) steps of DMA + weight prefetch
-    constexpr int VM_AFTER = NI * 4 + (XD - 1) * (JBE + NI * 4);
+    // The token tile of step kt+2 (not kt+1) is awaited at the end of step kt, so a tile is
+    // visible to every wavefront one whole step before it is used; the first fragments of step
+    // kt+1 can then be read during the last MFMA group of step kt and the MFMAs of the next step
+    // start right behind the barrier instead of behind an LDS round trip.
+    // Loads this wavefront issues after the DMA batch of step kt+2-XD and before the end of step
+    // kt: that step's weight prefetch, then (XD-2) steps of DMA + weight prefetch.
+    static_assert(XD >= 2, "needs the tile of step kt+2 in flight during step kt");
+    constexpr int VM_AFTER = NI * 4 + (XD - 2) * (JBE + NI * 4);
 
+    bf16x8 xnext[JBE];   // slot-0 fragments of the next step
     auto step = [&](int kt, auto u) {
         const int buf = kt % NBUF;
         constexpr int wst = (u + STAGES - 1) % STAGES;
         const int kw = phys(kt + STAGES - 1);
         dma_x(kt + XD, (kt + XD) % NBUF);   // the buffer read in step kt-1: free since that step's barrier
         bf16x8 xf[2][JBE];
-        static_for<JBE>([&](auto j) { xf[0][j] = frag(buf, j, std::integral_constant<int, 0>{}); });
+        static_for<JBE>([&](auto j) { xf[0][j] = xnext[j]; });
         __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
@@ -451,6 +457,11 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
                 if constexpr (i == 0 && s < 3) {
                     static_for<JBE>([&](auto j) {
                         xf[(s + 1) & 1][j] = frag(buf, j, std::integral_constant<int, s + 1>{});
+                    });
+                }
+                if constexpr (i == NI - 1 && s == 3) {   // last group: fragments for the next step
+                    static_for<JBE>([&](auto j) {
+                        xnext[j] = frag((kt + 1) % NBUF, j, std::integral_constant<int, 0>{});
                     });
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -461,15 +472,16 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
-        wait_vmcnt<VM_AFTER>();   // this wavefront's share of the token tile of step kt+1 has landed
+        wait_vmcnt<VM_AFTER>();   // this wavefront's share of the token tile of step kt+2 has landed
         __syncthreads();
     };
 
-    // prologue: token tiles of steps 0..XD-1, weights of steps 0..STAGES-2; step 0 must be complete
+    // prologue: token tiles of steps 0..XD-1, weights of steps 0..STAGES-2; tiles 0 and 1 complete
     static_for<XD>([&](auto q) { dma_x(q, q % NBUF); });
     static_for<STAGES - 1>([&](auto st) { load_w(st, st); });
-    wait_vmcnt<(XD - 1) * JBE + (STAGES - 1) * NI * 4>();
+    wait_vmcnt<(XD - 2) * JBE + (STAGES - 1) * NI * 4>();
     __syncthreads();
+    static_for<JBE>([&](auto j) { xnext[j] = frag(0, j, std::integral_constant<int, 0>{}); });
 
     constexpr int UNR = STAGES;
     int kt = 0;
