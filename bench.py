@@ -148,9 +148,11 @@ def main():
     counts = ws[lay.counts: lay.counts + 4 * s.E].view(torch.int32).cpu().numpy()
     e_active = int((counts > 0).sum())
     R = s.R
-    gate_up_bytes = 4 * s.d * s.F * e_active + 2 * R * s.d + 2 * R * s.F       # weights once, x_perm in, h out
+    gate_up_bytes = 4 * s.d * s.F * e_active + 2 * R * s.d + 2 * R * s.F       # weights once, token rows in, h out
     gate_up_flops = 4 * R * s.d * s.F
-    layer_bytes = (6 * s.d * s.F * e_active + 2 * s.E * s.d + 2 * s.T * s.d + 2 * 2 * R * s.d + 2 * 2 * R * s.F
+    # weights once, router weights, x (router), R gathered token rows (gate+up), h and y_perm written + read,
+    # y, index/weight arrays.  No permuted copy of x is written (the gather is folded into gate+up).
+    layer_bytes = (6 * s.d * s.F * e_active + 2 * s.E * s.d + 2 * s.T * s.d + 2 * R * s.d + 2 * 2 * R * s.F
                    + 2 * 2 * R * s.d + 2 * s.T * s.d + 16 * R)
     layer_flops = s.T * (6 * s.k * s.d * s.F + 2 * s.E * s.d)
     mean_rows = R / max(e_active, 1)

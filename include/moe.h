@@ -68,7 +68,7 @@ typedef struct {
     size_t offsets;   /* int32 [E+1] */
     size_t row_of;    /* int32 [R]   */
     size_t src_of;    /* int32 [R]   */
-    size_t x_perm;    /* bf16  [R,d] */
+    size_t x_perm;    /* zero-length: moe_forward reads x rows through src_of and writes no permuted copy */
     size_t h;         /* bf16  [R,F] */
     size_t y_perm;    /* bf16  [R,d] */
     size_t scratch;   /* internal: partial logit tiles, chunk histograms, block schedule */
@@ -160,14 +160,18 @@ moe_status moe_combine(const moe_config* cfg, const void* y_perm, const int32_t*
                        const float* topk_w, void* y, void* stream);
 
 /* The whole layer: stages 1-5 enqueued back to back on `stream`, intermediates in
- * `workspace` at moe_forward_workspace_layout()'s offsets.  y [T,d] bf16.  W_packed as above. */
+ * `workspace` at moe_forward_workspace_layout()'s offsets.  y [T,d] bf16.  W_packed as above.
+ * The permutation stage builds the index arrays only: the gate+up GEMM fetches expert-contiguous
+ * row r straight from x[src_of[r] / k] while it loads its token tile, so the permuted copy of x
+ * (Sec. 3.1 step 2; the paper lists removing it as future work) is never written.  Results are
+ * identical to moe_permute + moe_grouped_ffn on the materialised copy. */
 moe_status moe_forward(const moe_config* cfg, const void* x, const void* W_r, const float* bias,
                        const void* W_gate, const void* W_up, const void* W_down, const void* W_packed,
                        void* y, void* workspace, size_t ws_bytes, void* stream);
 
 /* moe_forward with timing hooks: `events` is an array of n_events hipEvent_t handles (as void*,
  * entries may be NULL, the array itself may be NULL when n_events == 0) recorded on `stream`
- *   [0] before the router, [1] after it, [2] after the permutation (index arrays + row gather),
+ *   [0] before the router, [1] after it, [2] after the permutation (index arrays; the row gather runs inside gate+up),
  *   [3] after the fused gate+up GEMM, [4] after the down GEMM, [5] after the combine.
  * Entries beyond index 5 are ignored.  Everything else is exactly moe_forward (Sec. 3.1's
  * five stages; the per-stage breakdown mirrors the paper's Table 6). */

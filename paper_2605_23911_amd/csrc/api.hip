@@ -1,5 +1,6 @@
 // C ABI of the library (include/moe.h): argument checks on the host, workspace layout, and
 // the stage launchers strung together.  Nothing here allocates, copies or synchronises.
+#include <cstdlib>
 #include <cmath>
 
 #include "moe_internal.hpp"
@@ -113,7 +114,7 @@ moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layou
     out->offsets = take((size_t)(c->E + 1) * sizeof(int32_t));
     out->row_of = take(R * sizeof(int32_t));
     out->src_of = take(R * sizeof(int32_t));
-    out->x_perm = take(R * c->d * sizeof(uint16_t));
+    out->x_perm = take(0);   // moe_forward gathers rows inside the gate+up loads: no permuted copy of x
     out->h = take(R * c->F * sizeof(uint16_t));
     out->y_perm = take(R * c->d * sizeof(uint16_t));
     out->scratch = take(moe_route_workspace_size(c) + hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
@@ -202,7 +203,7 @@ moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_
     const uint16_t* pdn = pgu ? pgu + packed_gate_up_bytes(*c) / sizeof(uint16_t) : nullptr;
     hipError_t e = launch_block_schedule(*c, offsets, M, blocks, num_blocks, s);
     if (e == hipSuccess)
-        e = launch_gate_up(*c, M, (const uint16_t*)x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
+        e = launch_gate_up(*c, M, (const uint16_t*)x_perm, nullptr, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
                            (const uint16_t*)W_up, pgu, (uint16_t*)h, s);
     if (e == hipSuccess)
         e = launch_down(*c, M, (const uint16_t*)h, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn,
@@ -247,7 +248,6 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     int32_t* offsets = (int32_t*)(ws + l.offsets);
     int32_t* row_of = (int32_t*)(ws + l.row_of);
     int32_t* src_of = (int32_t*)(ws + l.src_of);
-    uint16_t* x_perm = (uint16_t*)(ws + l.x_perm);
     uint16_t* h = (uint16_t*)(ws + l.h);
     uint16_t* y_perm = (uint16_t*)(ws + l.y_perm);
     void* route_ws = ws + l.scratch;
@@ -266,11 +266,12 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     mark(1);
     if (e == hipSuccess)
         e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);
-    if (e == hipSuccess) e = launch_gather_rows(*c, (const uint16_t*)x, src_of, x_perm, s);
     mark(2);
+    // The row gather of the permutation is folded into the gate+up tile loads (row r is read from
+    // x[src_of[r] / k]); the permuted copy of x that moe_permute can write is not needed here.
     if (e == hipSuccess)
-        e = launch_gate_up(*c, M, x_perm, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
-                           (const uint16_t*)W_up, pgu, h, s);
+        e = launch_gate_up(*c, M, (const uint16_t*)x, src_of, offsets, blocks, num_blocks,
+                           (const uint16_t*)W_gate, (const uint16_t*)W_up, pgu, h, s);
     mark(3);
     if (e == hipSuccess)
         e = launch_down(*c, M, h, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm, s);

@@ -55,7 +55,7 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
-    GemmArgs a{h, wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    GemmArgs a{h, nullptr, 1, wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
     const bool packed = packed_dn != nullptr;
     int id = env_variant("MOE_DN_VARIANT", kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);

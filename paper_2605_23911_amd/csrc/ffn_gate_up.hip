@@ -44,10 +44,11 @@ const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed) {
     return kGateUp[id].name;
 }
 
-hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm, const int32_t* offsets,
+hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, const int32_t* src_of,
+                          const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s) {
-    GemmArgs a{x_perm, wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
+    GemmArgs a{x_rows, src_of, c.k, wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
     const bool packed = packed_gu != nullptr;
     int id = env_variant("MOE_GU_VARIANT", kNumGateUp, M, packed, kGateUp);
     if (id < 0) id = pick(M, packed, c);

@@ -44,7 +44,9 @@ constexpr int kBK = 64;            // reduction elements per pipeline step
 constexpr int kLdsStride = 72;     // bf16 elements per staged token row: 64 + 8 pad (144 B)
 
 struct GemmArgs {
-    const uint16_t* X;          // [R, K] expert-contiguous rows
+    const uint16_t* X;          // [R, K] expert-contiguous rows, or the un-permuted [T, K] rows if src != nullptr
+    const int32_t* src;         // [R] flat (token, slot) index of every expert-contiguous row, or nullptr
+    int src_k;                  // slots per token: row r then lives at X[src[r] / src_k]
     const uint16_t* W0;         // [E, N, K]  gate (or down)
     const uint16_t* W1;         // [E, N, K]  up   (unused for down)
     const uint16_t* P;          // packed weights of this projection (PACKED kernels), else unused
@@ -107,6 +109,15 @@ struct WAddr {
         }
     }
 };
+
+// Address of expert-contiguous token row `row` (clamped to the last row).  With a source map the
+// permutation of Sec. 3.1 is applied here, in the load address, and the permuted copy of the
+// activations is never written.
+__device__ __forceinline__ const uint16_t* token_row(const GemmArgs& a, int row) {
+    row = row < a.R ? row : a.R - 1;
+    if (a.src != nullptr) row = a.src[row] / a.src_k;
+    return a.X + (size_t)row * a.K;
+}
 
 // Block schedule entry -> tile geometry (Alg. 1: block = (expert, row offset)).
 struct Tile {
@@ -191,9 +202,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     // token tile: thread -> (row tid/8 + XROWS*p, 16-byte chunk tid%8); rows clamped inside X
     const uint16_t* xp[XP];
     static_for<XP>([&](auto p) {
-        int row = t.row0 + (tid >> 3) + XROWS * p;
-        row = row < a.R ? row : a.R - 1;
-        xp[p] = a.X + (size_t)row * K + (tid & 7) * 8;
+        xp[p] = token_row(a, t.row0 + (tid >> 3) + XROWS * p) + (tid & 7) * 8;
     });
     const int xs_store = (tid >> 3) * kLdsStride + (tid & 7) * 8;
     const int xs_read = (tgrp * JW * 32 + li) * kLdsStride + half * 8;
@@ -389,10 +398,8 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     const uint16_t* xp[JBE];
     static_for<JBE>([&](auto q) {
         const int rg = q * 4 + wave;
-        int row = t.row0 + rg * 8 + (lane >> 3);
-        row = row < a.R ? row : a.R - 1;
         const int chunk = (lane & 7) ^ (((lane >> 3) ^ rg) & 7);
-        xp[q] = a.X + (size_t)row * K + chunk * 8;
+        xp[q] = token_row(a, t.row0 + rg * 8 + (lane >> 3)) + chunk * 8;
     });
     const uint32_t lds0 = (uint32_t)(uintptr_t)xs;            // LDS byte address of the ring
     const uint32_t dma_dst = lds0 + wave * 1024;              // + q*4096 + buffer*BUF_BYTES
@@ -585,9 +592,7 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
     static_for<NM>([&](auto m) { wp[m] = WA::base(a, t.e, n0w / 32, m, lane); });
     const uint16_t* xp[JB];
     static_for<JB>([&](auto j) {
-        int row = t.row0 + j * 32 + li;
-        row = row < a.R ? row : a.R - 1;
-        xp[j] = a.X + (size_t)row * K + half * 8;
+        xp[j] = token_row(a, t.row0 + j * 32 + li) + half * 8;
     });
 
     f32x16 acc[NM][JB];

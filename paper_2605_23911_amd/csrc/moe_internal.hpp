@@ -48,8 +48,11 @@ hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, in
                                  int32_t* blocks, int32_t* num_blocks, hipStream_t s);
 
 // packed_gu / packed_dn: the projection's region of moe_pack_weights' buffer, or nullptr to
-// read the row-major weights.
-hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_perm, const int32_t* offsets,
+// read the row-major weights.  gate+up reads expert-contiguous rows x_rows[R, d] when src_of is
+// nullptr; otherwise x_rows is the un-permuted x[T, d] and row r is fetched from token
+// src_of[r] / k (the gather of Sec. 3.1 folded into the tile load).
+hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, const int32_t* src_of,
+                          const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s);
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,

@@ -97,7 +97,6 @@ def run_forward(layer: Layer, tile_m: int = 0, packed: bool = True):
         offsets=view(lay.offsets, s.E + 1, torch.int32).cpu().numpy(),
         row_of=view(lay.row_of, R, torch.int32).cpu().numpy(),
         src_of=view(lay.src_of, R, torch.int32).cpu().numpy(),
-        x_perm=np_bits(view(lay.x_perm, R * s.d, torch.bfloat16)).reshape(R, s.d),
         h=np_bits(view(lay.h, R * s.F, torch.bfloat16)).reshape(R, s.F),
         y_perm=np_bits(view(lay.y_perm, R * s.d, torch.bfloat16)).reshape(R, s.d),
     )

@@ -53,8 +53,8 @@ def _check_routing(out, ref, layer):
     assert np.abs(out["topk_w"].astype(np.float64) - ref["topk_w"]).max() <= 1e-6
     for name in ("counts", "offsets", "row_of", "src_of"):
         assert np.array_equal(out[name], ref[name]), name
-    s = layer.shape
-    assert np.array_equal(out["x_perm"], orc.permute_rows(layer.x_bits, ref["src_of"], s.k))
+    # moe_forward folds the row gather into the gate+up loads and writes no x_perm; the copy that
+    # moe_permute makes is checked where that entry point is tested.
 
 
 def _check_floats(out, ref, layer, G, tokens=None):
