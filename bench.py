@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--config", default="mixtral", choices=sorted(mi.PRESETS))
     ap.add_argument("--T", type=int, default=512)
+    ap.add_argument("--shape", default="", help="d,F,E,k of a synthetic layer (softmax gating) instead of --config, "
+                                                "e.g. the expert-scaling ladder of the paper's Table 5")
     ap.add_argument("--skew", type=float, default=0.0)
     ap.add_argument("--tile-m", type=int, default=0)
     ap.add_argument("--seed", type=int, default=0)
@@ -82,7 +84,11 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    s = mi.PRESETS[args.config].with_T(args.T)
+    if args.shape:
+        d_, F_, E_, k_ = (int(v) for v in args.shape.split(","))
+        s = mi.MoEShape(f"d{d_}-F{F_}-E{E_}-k{k_}", args.T, d_, F_, E_, k_)
+    else:
+        s = mi.PRESETS[args.config].with_T(args.T)
     x_cpu, wr_cpu = mi.make_x(s, args.seed), mi.make_router(s, args.seed)
     bias_cpu = mi.skew_bias(s, args.skew, args.seed)
     x, wr = x_cpu.to(dev), wr_cpu.to(dev)
