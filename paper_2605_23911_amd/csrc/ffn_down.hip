@@ -41,6 +41,8 @@ int pick(int M, bool packed, const moe_config& c) {
     const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
     if (!packed) return once ? 14 : 0;
     if (once) return wide ? 13 : 12;
+    // experts spanning several row tiles: LDS-DMA token tile, two weight blocks per wavefront
+    if ((double)R / c.E > 192.0 && M == 256) return 11;
     return wide ? 4 : 3;
 }
 
@@ -52,10 +54,12 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
     return kDown[id].name;
 }
 
-hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
+hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
-    GemmArgs a{h, nullptr, 1, wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    // token rows are addressed with 32-bit byte offsets from the buffer's base
+    if ((unsigned long long)a.x_rows * (unsigned long long)ldh * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_dn != nullptr;
     int id = env_variant("MOE_DN_VARIANT", kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);

@@ -33,6 +33,8 @@ bool stream_once(const moe_config& c) {
 }
 int pick(int M, bool packed, const moe_config& c) {
     if (stream_once(c)) return packed ? 10 : 11;
+    // experts spanning several row tiles: the LDS-DMA token tile (deeper prefetch, no staging registers)
+    if (packed && (double)c.T * c.k / c.E > 192.0 && M == 256) return 9;
     return packed ? 3 : 0;
 }
 
@@ -44,11 +46,13 @@ const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed) {
     return kGateUp[id].name;
 }
 
-hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, const int32_t* src_of,
-                          const int32_t* offsets,
+hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, int32_t ldx, const int32_t* src_of,
+                          int32_t ldh, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s) {
-    GemmArgs a{x_rows, src_of, c.k, wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
+    GemmArgs a{x_rows, src_of, c.k, src_of ? c.T : c.T * c.k, ldx, ldh, rot_steps(false), wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
+    // token rows are addressed with 32-bit byte offsets from the buffer's base
+    if ((unsigned long long)a.x_rows * (unsigned long long)ldx * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_gu != nullptr;
     int id = env_variant("MOE_GU_VARIANT", kNumGateUp, M, packed, kGateUp);
     if (id < 0) id = pick(M, packed, c);

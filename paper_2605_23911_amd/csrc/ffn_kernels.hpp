@@ -47,6 +47,9 @@ struct GemmArgs {
     const uint16_t* X;          // [R, K] expert-contiguous rows, or the un-permuted [T, K] rows if src != nullptr
     const int32_t* src;         // [R] flat (token, slot) index of every expert-contiguous row, or nullptr
     int src_k;                  // slots per token: row r then lives at X[src[r] / src_k]
+    int x_rows;                 // rows of X (T with a source map, else R); x_rows * ldx * 2 bytes < 4 GiB
+    int ldx, ldo;               // row strides of X and Out in elements (>= K and >= N)
+    int rot_mul;                // k-loop rotation between workgroups of one XCD, in steps (see tile_body)
     const uint16_t* W0;         // [E, N, K]  gate (or down)
     const uint16_t* W1;         // [E, N, K]  up   (unused for down)
     const uint16_t* P;          // packed weights of this projection (PACKED kernels), else unused
@@ -90,33 +93,81 @@ __device__ __forceinline__ float silu_mul(float g, float u) {
     return g * __frcp_rn(1.0f + __expf(-g)) * u;
 }
 
+// Buffer addressing (buffer_load_dwordx4 ... offen): address = descriptor base (scalar) + scalar
+// offset + per-lane 32-bit offset + immediate.  The per-step advance along k is the scalar offset
+// and the per-lane offset never changes, so the loads of the reduction loop need no vector
+// address arithmetic and no 64-bit address registers.  Offsets beyond the descriptor's range
+// read as zero instead of faulting.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);   // raw, 32-bit data format
+}
+template <bool NT>
+__device__ __forceinline__ uint4 buffer_load16(rsrc_t r, uint32_t lane_off, uint32_t scalar_off) {
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, scalar_off, NT ? 2 : 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 // Weight fragment addressing.  Unpacked: row-major rows, element (row, k).  Packed: 16-byte
 // units ordered [expert][row block][k step][matrix][s][lane].
 template <bool PACKED, int NM>
 struct WAddr {
     static constexpr int kStep = PACKED ? NM * 4 * 512 : kBK;   // elements per 64-wide k step
     static constexpr int sStep = PACKED ? 512 : 16;              // elements per MFMA slot s
-    __device__ static __forceinline__ const uint16_t* base(const GemmArgs& a, int e, int row_block, int m, int lane) {
-        const int li = lane & 31, half = lane >> 5;
-        const int nrb = a.N / 32;
+    // A fragment address is block() + lane_bytes(): block() is the same for the whole wavefront
+    // (it lives in scalar registers and the per-step advance is scalar arithmetic), lane_bytes()
+    // is a 32-bit per-lane offset that never changes, so a load needs no per-step vector
+    // address arithmetic and no 64-bit address registers.
+    __device__ static __forceinline__ int clamp_block(const GemmArgs& a, int row_block) {
+        const int last = PACKED ? a.N / 32 - 1 : (a.N - 1) / 32;   // ragged last feature tile: stores are masked
+        return row_block < last ? row_block : last;
+    }
+    __device__ static __forceinline__ const uint16_t* block(const GemmArgs& a, int e, int row_block, int m) {
+        const int rb = clamp_block(a, row_block);
+        if constexpr (PACKED)
+            return a.P + ((size_t)e * (a.N / 32) + rb) * (size_t)(a.K / kBK) * kStep + m * 4 * 512;
+        else
+            return (m == 0 ? a.W0 : a.W1) + ((size_t)e * a.N + rb * 32) * a.K;
+    }
+    // bytes from block() to the end of the rows / packed region it belongs to (buffer range)
+    __device__ static __forceinline__ uint32_t block_bytes(const GemmArgs& a, int row_block, int m) {
         if constexpr (PACKED) {
-            const int rb = row_block < nrb ? row_block : nrb - 1;   // ragged last feature tile
-            return a.P + ((size_t)e * nrb + rb) * (size_t)(a.K / kBK) * kStep + m * 4 * 512 + lane * 8;
+            return (uint32_t)(a.K / kBK) * kStep * 2u - (uint32_t)m * 4096u;
         } else {
-            int row = row_block * 32 + li;
-            row = row < a.N ? row : a.N - 1;
-            return (m == 0 ? a.W0 : a.W1) + ((size_t)e * a.N + row) * a.K + half * 8;
+            const int rows = a.N - clamp_block(a, row_block) * 32;
+            return (uint32_t)(rows < 32 ? rows : 32) * (uint32_t)a.K * 2u;
         }
+    }
+    __device__ static __forceinline__ uint32_t lane_bytes(const GemmArgs& a, int row_block, int lane) {
+        if constexpr (PACKED) {
+            return (uint32_t)lane * 16u;
+        } else {
+            const int li = lane & 31, half = lane >> 5;
+            const int rb = clamp_block(a, row_block);
+            int row = rb * 32 + li;
+            row = (row < a.N ? row : a.N - 1) - rb * 32;
+            return (uint32_t)(row * a.K + half * 8) * 2u;
+        }
+    }
+    __device__ static __forceinline__ const uint16_t* base(const GemmArgs& a, int e, int row_block, int m, int lane) {
+        return block(a, e, row_block, m) + lane_bytes(a, row_block, lane) / 2;
     }
 };
 
 // Address of expert-contiguous token row `row` (clamped to the last row).  With a source map the
 // permutation of Sec. 3.1 is applied here, in the load address, and the permuted copy of the
 // activations is never written.
-__device__ __forceinline__ const uint16_t* token_row(const GemmArgs& a, int row) {
+__device__ __forceinline__ int token_row_index(const GemmArgs& a, int row) {
     row = row < a.R ? row : a.R - 1;
     if (a.src != nullptr) row = a.src[row] / a.src_k;
-    return a.X + (size_t)row * a.K;
+    return row;
+}
+__device__ __forceinline__ const uint16_t* token_row(const GemmArgs& a, int row) {
+    return a.X + (size_t)token_row_index(a, row) * a.ldx;
+}
+// Byte offset of a token row from a.X as 32 bits (the launchers refuse buffers of 4 GiB or more).
+__device__ __forceinline__ uint32_t token_row_bytes(const GemmArgs& a, int row) {
+    return (uint32_t)token_row_index(a, row) * (uint32_t)a.ldx * 2u;
 }
 
 // Block schedule entry -> tile geometry (Alg. 1: block = (expert, row offset)).
@@ -187,22 +238,34 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     constexpr int XROWS = NTHR / 8;             // token rows staged per pass (8 threads x 16 B per row)
     constexpr int XP = (JBE * 32) / XROWS;      // passes per step
     static_assert(JBE % TH == 0 && (JBE * 32) % XROWS == 0, "token tile must split evenly");
-    const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+    const int tid = threadIdx.x, lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform: scalar register
     const int li = lane & 31, half = lane >> 5;
     const int wrow = wave & 3, tgrp = wave >> 2;
     const int K = a.K, N = a.N;
     const int KT = K / kBK;
     const int n0w = nt * BN + wrow * (IB * 32);
 
+    // Weight fragments: scalar block base per (matrix, row block) + one per-lane byte offset.
+    // Out-of-range rows of a ragged last feature tile are clamped, their stores masked.
     typedef WAddr<PACKED, NM> WA;
-    const uint16_t* wp[NI];   // out-of-range rows of a ragged last feature tile are clamped, stores masked
+    rsrc_t wb[NI];
+    uint32_t wl[PACKED ? 1 : IB];
     static_for<NM>([&](auto m) {
-        static_for<IB>([&](auto ib) { wp[m * IB + ib] = WA::base(a, t.e, n0w / 32 + ib, m, lane); });
+        static_for<IB>([&](auto ib) {
+            wb[m * IB + ib] = make_rsrc(WA::block(a, t.e, n0w / 32 + ib, m), WA::block_bytes(a, n0w / 32 + ib, m));
+        });
     });
-    // token tile: thread -> (row tid/8 + XROWS*p, 16-byte chunk tid%8); rows clamped inside X
-    const uint16_t* xp[XP];
+    static_for<(PACKED ? 1 : IB)>([&](auto ib) { wl[ib] = WA::lane_bytes(a, n0w / 32 + ib, lane); });
+    auto w_load = [&](auto i, int kc, auto s) {
+        return buffer_load16<WNT>(wb[i], wl[PACKED ? 0 : i % IB] + s * (WA::sStep * 2), (uint32_t)kc * (WA::kStep * 2));
+    };
+    const rsrc_t xb = make_rsrc(a.X, (uint32_t)a.x_rows * (uint32_t)a.ldx * 2u);
+    // token tile: thread -> (row tid/8 + XROWS*p, 16-byte chunk tid%8); rows clamped inside X.
+    // Scalar base a.X + k offset, per-thread 32-bit byte offsets fixed for the whole loop.
+    uint32_t xo[XP];
     static_for<XP>([&](auto p) {
-        xp[p] = token_row(a, t.row0 + (tid >> 3) + XROWS * p) + (tid & 7) * 8;
+        xo[p] = token_row_bytes(a, t.row0 + (tid >> 3) + XROWS * p) + (uint32_t)(tid & 7) * 16u;
     });
     const int xs_store = (tid >> 3) * kLdsStride + (tid & 7) * 8;
     const int xs_read = (tgrp * JW * 32 + li) * kLdsStride + half * 8;
@@ -224,7 +287,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     // length is (d = 4096, F = 14336, ...), so they sit in the same L2 channel; workgroups that
     // run together on an XCD (ids 8 apart) start two steps apart and so spread over the channels
     // instead of all hammering the same one.  The sum over k does not care about the order.
-    const int rot = (int)(((blockIdx.x >> 3) * 2u) % (unsigned)KT);
+    const int rot = (int)(((blockIdx.x >> 3) * (unsigned)a.rot_mul) % (unsigned)KT);
     auto phys = [&](int i) {
         int p = (i < KT ? i : KT - 1) + rot;
         return p >= KT ? p - KT : p;
@@ -240,14 +303,14 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         const int kc = phys(kt);
         static_for<NI>([&](auto i) {
             static_for<4>([&](auto s) {
-                wreg[st][i][s] = load_w16<WNT>(wp[i] + (size_t)kc * WA::kStep + s * WA::sStep);
+                wreg[st][i][s] = w_load(i, kc, s);
             });
         });
     };
     auto load_x = [&](int kt, auto xs_) {
-        const int kc = phys(kt);
+        const uint32_t kb = (uint32_t)phys(kt) * (kBK * 2);
         static_for<XP>([&](auto p) {
-            const uint4 v = *reinterpret_cast<const uint4*>(xp[p] + (size_t)kc * kBK);
+            const uint4 v = buffer_load16<false>(xb, xo[p], kb);
             xreg[xs_][4 * p + 0] = v.x;
             xreg[xs_][4 * p + 1] = v.y;
             xreg[xs_][4 * p + 2] = v.z;
@@ -288,7 +351,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         MOE_TICK(0)
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
-                wreg[wst][i][s] = load_w16<WNT>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                wreg[wst][i][s] = w_load(i, kw, s);
                 if constexpr (i == 0 && s < 3) {
                     static_for<JW>([&](auto j) {
                         xf[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
@@ -345,7 +408,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         static_for<JW>([&](auto j) {
             const int tr = (tgrp * JW + j) * 32 + li;
             if (tr < t.rows)
-                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * N,
+                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * a.ldo,
                                     n0w + ib * 32, half, N);
         });
     });
@@ -420,7 +483,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     });
     uint4 wreg[STAGES][NI][4];
 
-    const int rot = (int)(((blockIdx.x >> 3) * 2u) % (unsigned)KT);   // see tile_body
+    const int rot = (int)(((blockIdx.x >> 3) * (unsigned)a.rot_mul) % (unsigned)KT);   // see tile_body
     auto phys = [&](int i) {
         int p = (i < KT ? i : KT - 1) + rot;
         return p >= KT ? p - KT : p;
@@ -444,23 +507,33 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     // visible to every wavefront one whole step before it is used; the first fragments of step
     // kt+1 can then be read during the last MFMA group of step kt and the MFMAs of the next step
     // start right behind the barrier instead of behind an LDS round trip.
-    // Loads this wavefront issues after the DMA batch of step kt+2-XD and before the end of step
-    // kt: that step's weight prefetch, then (XD-2) steps of DMA + weight prefetch.
+    // The DMA instructions of a step are dealt over its MFMA groups (group g takes q = g, g+NG,
+    // ...) behind that group's weight load: the CU's one address unit needs 16 cycles per
+    // 64-lane 16-byte access, and a burst of JBE of them from all four wavefronts at once would
+    // hold every instruction stream (and so the MFMAs) for several hundred cycles per step.
+    // Loads this wavefront issues after its last DMA of step kt+2-XD and before the end of step
+    // kt: the weight loads of the groups behind that DMA, then (XD-2) whole steps.
     static_assert(XD >= 2, "needs the tile of step kt+2 in flight during step kt");
-    constexpr int VM_AFTER = NI * 4 + (XD - 2) * (JBE + NI * 4);
+    constexpr int NG = 4 * NI;                                   // MFMA groups = weight loads per step
+    constexpr int G_LAST = (JBE < NG ? JBE : NG) - 1;            // last group that issues a DMA
+    constexpr int VM_AFTER = (NG - 1 - G_LAST) + (XD - 2) * (NG + JBE);
 
     bf16x8 xnext[JBE];   // slot-0 fragments of the next step
     auto step = [&](int kt, auto u) {
         const int buf = kt % NBUF;
         constexpr int wst = (u + STAGES - 1) % STAGES;
         const int kw = phys(kt + STAGES - 1);
-        dma_x(kt + XD, (kt + XD) % NBUF);   // the buffer read in step kt-1: free since that step's barrier
+        const int kx = phys(kt + XD);
+        const uint32_t dst = dma_dst + ((kt + XD) % NBUF) * BUF_BYTES;   // the buffer read in step kt-1: free since that step's barrier
         bf16x8 xf[2][JBE];
         static_for<JBE>([&](auto j) { xf[0][j] = xnext[j]; });
         __builtin_amdgcn_sched_barrier(0);
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
                 wreg[wst][i][s] = load_w16<WNT>(wp[i] + (size_t)kw * WA::kStep + s * WA::sStep);
+                static_for<JBE>([&](auto q) {
+                    if constexpr (q % NG == s * NI + i) lds_dma16(xp[q] + (size_t)kx * kBK, dst + q * 4096);
+                });
                 if constexpr (i == 0 && s < 3) {
                     static_for<JBE>([&](auto j) {
                         xf[(s + 1) & 1][j] = frag(buf, j, std::integral_constant<int, s + 1>{});
@@ -502,7 +575,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
         static_for<JBE>([&](auto j) {
             const int tr = j * 32 + li;
             if (tr < t.rows)
-                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * N,
+                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * a.ldo,
                                     n0w + ib * 32, half, N);
         });
     });
@@ -557,7 +630,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
         case 4: return tile_body_dma<8, 4, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
         case 5: return tile_body_dma<8, 5, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
         case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
-        default: return tile_body_dma<8, 8, IB, GATEUP, NI >= 2 ? 2 : 3, 3, PACKED>(a, t, nt, xs);
+        default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED>(a, t, nt, xs);
     }
 }
 
@@ -668,7 +741,7 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
     static_for<JB>([&](auto j) {
         const int tr = j * 32 + li;
         if (tr < t.rows)
-            store_block<GATEUP>(acc[0][j], acc[GATEUP ? 1 : 0][j], a.Out + (size_t)(t.row0 + tr) * N, n0w, half, N);
+            store_block<GATEUP>(acc[0][j], acc[GATEUP ? 1 : 0][j], a.Out + (size_t)(t.row0 + tr) * a.ldo, n0w, half, N);
     });
 }
 
@@ -676,6 +749,17 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
 // launch helpers
 // =============================================================================================
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
+
+// k-loop rotation between the workgroups of an XCD, in steps.  Single-block experts (weights
+// streamed once): 2, which spreads the row-strided token tile reads over the L2 channels.
+// Multi-tile experts (the LDS-DMA kernels): 0, so that row tiles that share a weight panel, and
+// feature tiles that share a token tile, walk k together and meet in L2 (measured: a third
+// fewer L2 misses, ~3 % faster at Mixtral T=4096).
+inline int rot_steps(bool dma) {
+    static const int v = std::getenv("MOE_ROT") ? std::atoi(std::getenv("MOE_ROT")) : -1;
+    return v >= 0 ? v : (dma ? 0 : 2);
+}
+
 
 template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW = 4, bool WNT = false>
 hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
@@ -712,6 +796,7 @@ hipError_t launch_tile_dma(const GemmArgs& a, int max_blocks, hipStream_t s) {
     if (attr != hipSuccess) return attr;
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
+    args.rot_mul = rot_steps(true);
     const long long grid = (long long)max_blocks * args.n_tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();

@@ -43,7 +43,7 @@ hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, in
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
                                 int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s);
 hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int32_t* src_of,
-                              uint16_t* x_perm, hipStream_t s);
+                              uint16_t* x_perm, int32_t ld_perm, hipStream_t s);
 hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M,
                                  int32_t* blocks, int32_t* num_blocks, hipStream_t s);
 
@@ -51,11 +51,12 @@ hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, in
 // read the row-major weights.  gate+up reads expert-contiguous rows x_rows[R, d] when src_of is
 // nullptr; otherwise x_rows is the un-permuted x[T, d] and row r is fetched from token
 // src_of[r] / k (the gather of Sec. 3.1 folded into the tile load).
-hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, const int32_t* src_of,
-                          const int32_t* offsets,
+// ldx / ldh: row strides (elements) of x_rows and of h.
+hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows, int32_t ldx, const int32_t* src_of,
+                          int32_t ldh, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s);
-hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, const int32_t* offsets,
+hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s);
 

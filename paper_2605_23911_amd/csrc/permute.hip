@@ -286,11 +286,11 @@ __global__ __launch_bounds__(kFusedThreads) void fused_permute_kernel(
 // ---- 4. row gather ------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __restrict__ x,
                                                          const int32_t* __restrict__ src_of, int k, int d,
-                                                         uint16_t* __restrict__ x_perm) {
+                                                         uint16_t* __restrict__ x_perm, int ld_perm) {
     const int r = blockIdx.x;
     const int t = src_of[r] / k;
     const uint4* src = reinterpret_cast<const uint4*>(x + (size_t)t * d);
-    uint4* dst = reinterpret_cast<uint4*>(x_perm + (size_t)r * d);
+    uint4* dst = reinterpret_cast<uint4*>(x_perm + (size_t)r * ld_perm);
     for (int v = threadIdx.x; v < d / 8; v += kThreads) dst[v] = src[v];
 }
 
@@ -315,8 +315,8 @@ hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, in
 }
 
 hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int32_t* src_of,
-                              uint16_t* x_perm, hipStream_t s) {
-    hipLaunchKernelGGL(gather_kernel, dim3(c.T * c.k), dim3(kThreads), 0, s, x, src_of, c.k, c.d, x_perm);
+                              uint16_t* x_perm, int32_t ld_perm, hipStream_t s) {
+    hipLaunchKernelGGL(gather_kernel, dim3(c.T * c.k), dim3(kThreads), 0, s, x, src_of, c.k, c.d, x_perm, ld_perm);
     return hipGetLastError();
 }
 
