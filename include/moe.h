@@ -68,13 +68,11 @@ typedef struct {
     size_t offsets;   /* int32 [E+1] */
     size_t row_of;    /* int32 [R]   */
     size_t src_of;    /* int32 [R]   */
-    size_t x_perm;    /* bf16 [R, x_perm_ld]; zero-length when x_perm_ld == 0 (rows read through src_of) */
-    size_t h;         /* bf16 [R, h_ld], columns 0..F-1 of each row are valid */
+    size_t x_perm;    /* zero-length: moe_forward reads x rows through src_of and writes no permuted copy */
+    size_t h;         /* bf16  [R,F] */
     size_t y_perm;    /* bf16  [R,d] */
     size_t scratch;   /* internal: partial logit tiles, chunk histograms, block schedule */
     size_t total;     /* bytes needed */
-    size_t x_perm_ld; /* row stride of x_perm in elements (>= d), or 0: no permuted copy of x is made */
-    size_t h_ld;      /* row stride of h in elements (>= F) */
 } moe_workspace_layout;
 
 const char* moe_status_string(moe_status s);

@@ -42,7 +42,7 @@ class MoEConfig(C.Structure):
 
 class WorkspaceLayout(C.Structure):
     _fields_ = [(n, C.c_size_t) for n in ("topk_idx", "topk_w", "counts", "offsets", "row_of", "src_of",
-                                          "x_perm", "h", "y_perm", "scratch", "total", "x_perm_ld", "h_ld")]
+                                          "x_perm", "h", "y_perm", "scratch", "total")]
 
 
 def library_path() -> str:

@@ -101,19 +101,6 @@ size_t moe_ffn_workspace_size(const moe_config* c) {
     return check_config(c) == MOE_OK ? schedule_bytes(c, moe_tile_m(c)) : 0;
 }
 
-// Row strides of moe_forward's activation buffers.  Rows whose length is a multiple of 4 KiB
-// (d = 4096, F = 14336, ...) would put one k step of EVERY row of a token tile into the same L2
-// channel; 256 bytes of padding per row rotates consecutive rows over the channels, which lets
-// the workgroups of an XCD walk k in step and share token tiles and weight panels through L2.
-static int padded_ld(int n) { return (n % 128 == 0 && (n / 128) % 2 == 0) ? n + 128 : n; }
-// Experts that span several row tiles (weight panels re-used through L2): gather x into a padded
-// copy.  Single-block experts stream their weights once and read x rows through src_of.
-static bool materialise_x(const moe_config* c) {
-    static const int force = std::getenv("MOE_PAD") ? std::atoi(std::getenv("MOE_PAD")) : -1;
-    if (force >= 0) return force != 0;
-    return false;
-}
-
 moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layout* out) {
     const moe_status st = check_config(c);
     if (st != MOE_OK) return st;
@@ -127,10 +114,8 @@ moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layou
     out->offsets = take((size_t)(c->E + 1) * sizeof(int32_t));
     out->row_of = take(R * sizeof(int32_t));
     out->src_of = take(R * sizeof(int32_t));
-    out->x_perm_ld = materialise_x(c) ? (size_t)padded_ld(c->d) : 0;
-    out->h_ld = materialise_x(c) ? (size_t)padded_ld(c->F) : (size_t)c->F;
-    out->x_perm = take(R * out->x_perm_ld * sizeof(uint16_t));
-    out->h = take(R * out->h_ld * sizeof(uint16_t));
+    out->x_perm = take(0);   // moe_forward gathers rows inside the gate+up loads: no permuted copy of x
+    out->h = take(R * c->F * sizeof(uint16_t));
     out->y_perm = take(R * c->d * sizeof(uint16_t));
     out->scratch = take(moe_route_workspace_size(c) + hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
     out->total = off;
@@ -281,19 +266,15 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     mark(1);
     if (e == hipSuccess)
         e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);
-    // Either the row gather is folded into the gate+up tile loads (row r is read from
-    // x[src_of[r] / k], no permuted copy of x), or x is gathered into a copy with padded rows.
-    const bool copy_x = l.x_perm_ld != 0;
-    if (copy_x && e == hipSuccess)
-        e = launch_gather_rows(*c, (const uint16_t*)x, src_of, (uint16_t*)(ws + l.x_perm), (int32_t)l.x_perm_ld, s);
     mark(2);
+    // The row gather of the permutation is folded into the gate+up tile loads (row r is read from
+    // x[src_of[r] / k]); the permuted copy of x that moe_permute can write is not needed here.
     if (e == hipSuccess)
-        e = launch_gate_up(*c, M, copy_x ? (const uint16_t*)(ws + l.x_perm) : (const uint16_t*)x,
-                           copy_x ? (int32_t)l.x_perm_ld : c->d, copy_x ? nullptr : src_of, (int32_t)l.h_ld, offsets,
-                           blocks, num_blocks, (const uint16_t*)W_gate, (const uint16_t*)W_up, pgu, h, s);
+        e = launch_gate_up(*c, M, (const uint16_t*)x, c->d, src_of, c->F, offsets, blocks, num_blocks,
+                           (const uint16_t*)W_gate, (const uint16_t*)W_up, pgu, h, s);
     mark(3);
     if (e == hipSuccess)
-        e = launch_down(*c, M, h, (int32_t)l.h_ld, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm, s);
+        e = launch_down(*c, M, h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm, s);
     mark(4);
     if (e == hipSuccess) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);
     mark(5);

@@ -97,7 +97,7 @@ def run_forward(layer: Layer, tile_m: int = 0, packed: bool = True):
         offsets=view(lay.offsets, s.E + 1, torch.int32).cpu().numpy(),
         row_of=view(lay.row_of, R, torch.int32).cpu().numpy(),
         src_of=view(lay.src_of, R, torch.int32).cpu().numpy(),
-        h=np_bits(view(lay.h, R * lay.h_ld, torch.bfloat16)).reshape(R, lay.h_ld)[:, :s.F],
+        h=np_bits(view(lay.h, R * s.F, torch.bfloat16)).reshape(R, s.F),
         y_perm=np_bits(view(lay.y_perm, R * s.d, torch.bfloat16)).reshape(R, s.d),
     )
     return out

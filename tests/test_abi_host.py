@@ -82,14 +82,13 @@ def test_workspace_layout_is_ordered_and_sized(L):
     for T, d, F, E, k in [(64, 256, 512, 8, 2), (512, 4096, 14336, 8, 2), (4096, 7168, 2048, 256, 8), (1, 64, 64, 1, 1)]:
         c = moe.MoEConfig.of(T, d, F, E, k)
         l = moe.forward_workspace_layout(c)
-        names = [n for n, _ in l._fields_ if n not in ("total", "x_perm_ld", "h_ld")]
+        names = [n for n, _ in l._fields_ if n != "total"]
         offs = [getattr(l, n) for n in names]
         assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
         R = T * k
-        assert l.h_ld >= F and l.x_perm_ld in (0, d, d + 128) and l.h_ld in (F, F + 128)
-        assert l.h - l.x_perm >= R * l.x_perm_ld * 2 and l.y_perm - l.h >= R * l.h_ld * 2
+        assert l.h >= l.x_perm and l.y_perm - l.h >= R * F * 2
         assert l.total == moe.forward_workspace_size(c) >= l.scratch + moe.ffn_workspace_size(c) + moe.route_workspace_size(c)
-        assert l.total < 2 * R * (2 * d + F + 256) + (8 << 20) + 16 * R + 4 * E * (R // 1024 + 1) * 2 + 8 * (T + 16) * (E + 16)
+        assert l.total < 2 * R * (2 * d + F) + (8 << 20) + 16 * R + 4 * E * (R // 1024 + 1) * 2 + 8 * (T + 16) * (E + 16)
 
 
 def test_max_blocks_bounds_algorithm_1(L):
