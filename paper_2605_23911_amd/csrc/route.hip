@@ -16,6 +16,7 @@
 //   one token and eight experts; each unit writes its 16x16 fp64 partial tile.
 // Kernel 2 (gate + top-k): one wavefront per token sums the slices, applies the gate and
 //   selects k experts.
+// Models with at most 16 experts take a single kernel instead (route_direct_kernel).
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -127,40 +128,20 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __rest
     }
 }
 
-// ---- kernel 2: gate + top-k, one wavefront per token ------------------------------------------
-__global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict__ part,
-                                                       const float* __restrict__ bias,
-                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                                       int T, int E, int k, int gating, int T16, int E16, int KS) {
-    __shared__ double wsel[kWavesPerBlock][kMaxExperts];
-    __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
-    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-    const int t = blockIdx.x * kWavesPerBlock + wave;
-    if (t >= T) return;
-
-    constexpr int Q = kMaxExperts / kWave;   // logits per lane
+// ---- gate + top-k of one token by one wavefront ---------------------------------------------
+// Lane l holds the logits of experts l, l+64, ... in z[] (ok[] = expert exists).  Eq. 1-2,
+// Sec. 3.4: max-subtracted softmax (or sigmoid), k rounds of arg-max over the logits with the
+// winners masked, ties to the lower index.
+constexpr int kLogitsPerLane = kMaxExperts / kWave;
+__device__ __forceinline__ void gate_and_select(double (&z)[kLogitsPerLane], const bool (&ok)[kLogitsPerLane],
+                                                int lane, int wave, int t, int k, int gating,
+                                                double (*wsel)[kMaxExperts], int32_t (*sel_idx)[kMaxExperts],
+                                                int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    constexpr int Q = kLogitsPerLane;
     const double ninf = -__builtin_huge_val();
-    const size_t EP = (size_t)E16 * 16;
-    double z[Q], p[Q];
-    bool ok[Q];
+    double p[Q];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        const int e = lane + kWave * q;
-        ok[q] = e < E;
-        double v = ninf;
-        if (ok[q]) {
-            v = bias ? (double)bias[e] : 0.0;
-            for (int s0 = 0; s0 < KS; s0 += 8) {   // slices in fixed order; 8 independent loads at a time
-                double tmp[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u)
-                    tmp[u] = (s0 + u < KS) ? part[((size_t)(s0 + u) * T16 * 16 + t) * EP + e] : 0.0;
-#pragma unroll
-                for (int u = 0; u < 8; ++u) v += tmp[u];
-            }
-        }
-        z[q] = (v != v) ? ninf : v;   // a NaN logit can never win and never breaks the index range
-    }
+    for (int q = 0; q < Q; ++q) z[q] = (z[q] != z[q]) ? ninf : z[q];   // a NaN logit can never win and never breaks the index range
     double m = ninf;
 #pragma unroll
     for (int q = 0; q < Q; ++q) m = fmax(m, z[q]);
@@ -223,6 +204,118 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict
     }
 }
 
+// ---- kernel 2: gate + top-k, one wavefront per token ------------------------------------------
+__global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict__ part,
+                                                       const float* __restrict__ bias,
+                                                       int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                       int T, int E, int k, int gating, int T16, int E16, int KS) {
+    __shared__ double wsel[kWavesPerBlock][kMaxExperts];
+    __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int t = blockIdx.x * kWavesPerBlock + wave;
+    if (t >= T) return;
+
+    constexpr int Q = kLogitsPerLane;
+    const double ninf = -__builtin_huge_val();
+    const size_t EP = (size_t)E16 * 16;
+    double z[Q];
+    bool ok[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const int e = lane + kWave * q;
+        ok[q] = e < E;
+        double v = ninf;
+        if (ok[q]) {
+            v = bias ? (double)bias[e] : 0.0;
+            for (int s0 = 0; s0 < KS; s0 += 8) {   // slices in fixed order; 8 independent loads at a time
+                double tmp[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    tmp[u] = (s0 + u < KS) ? part[((size_t)(s0 + u) * T16 * 16 + t) * EP + e] : 0.0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v += tmp[u];
+            }
+        }
+        z[q] = v;
+    }
+    gate_and_select(z, ok, lane, wave, t, k, gating, wsel, sel_idx, topk_idx, topk_w);
+}
+
+// ---- few experts (E <= 16): the whole router in one kernel, one workgroup per token ----------
+// With 8 or 16 experts a 16x16 MFMA tile would be mostly padding and the two-kernel path costs
+// two launches for a few microseconds of work.  Here thread i takes 8 consecutive k of every
+// 2048, multiplies them with the same k of all E router rows in fp64 (bf16 -> fp64 is exact, so
+// are the products); butterfly sums and one LDS exchange leave the logits in wavefront 0, which
+// applies the gate and selects.  All loads of a thread are issued before the first use.
+template <int EB>
+__global__ __launch_bounds__(kThreads) void route_direct_kernel(const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ wr,
+                                                               const float* __restrict__ bias,
+                                                               int32_t* __restrict__ topk_idx,
+                                                               float* __restrict__ topk_w, int d, int E, int k,
+                                                               int gating) {
+    __shared__ double wsel[kWavesPerBlock][kMaxExperts];
+    __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
+    __shared__ double partial[kWavesPerBlock][EB];
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+    const int t = blockIdx.x;
+    double acc[EB];
+#pragma unroll
+    for (int e = 0; e < EB; ++e) acc[e] = 0.0;
+    const uint16_t* xr = x + (size_t)t * d;
+    for (int k0 = threadIdx.x * 8; k0 < d; k0 += 2 * kThreads * 8) {
+        // two chunks per trip (the second clamped to the first when it falls beyond d)
+        const int k1 = k0 + kThreads * 8;
+        const bool two = k1 < d;
+        const int k1c = two ? k1 : k0;
+        uint4 xa = *reinterpret_cast<const uint4*>(xr + k0), xb = *reinterpret_cast<const uint4*>(xr + k1c);
+        uint4 wa[EB], wb[EB];
+#pragma unroll
+        for (int e = 0; e < EB; ++e) {   // rows beyond E re-read the last row; their sums are never used
+            const uint16_t* row = wr + (size_t)(e < E ? e : E - 1) * d;
+            wa[e] = *reinterpret_cast<const uint4*>(row + k0);
+            wb[e] = *reinterpret_cast<const uint4*>(row + k1c);
+        }
+        double xv[8], yv[8];
+        unpack8(xa, xv);
+        unpack8(xb, yv);
+#pragma unroll
+        for (int e = 0; e < EB; ++e) {
+            double w8[8];
+            unpack8(wa[e], w8);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[e] = fma(xv[j], w8[j], acc[e]);
+            unpack8(wb[e], w8);
+            double a2 = 0.0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) a2 = fma(yv[j], w8[j], a2);
+            acc[e] += two ? a2 : 0.0;
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < EB; ++e) {
+        const double tot = wave_sum(acc[e]);
+        if (lane == 0) partial[wave][e] = tot;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    constexpr int Q = kLogitsPerLane;
+    double z[Q];
+    bool ok[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        ok[q] = q == 0 && lane < E;
+        z[q] = -__builtin_huge_val();
+    }
+    if (ok[0]) {
+        double v = bias ? (double)bias[lane] : 0.0;
+#pragma unroll
+        for (int w = 0; w < kWavesPerBlock; ++w) v += partial[w][lane];
+        z[0] = v;
+    }
+    gate_and_select(z, ok, lane, 0, t, k, gating, wsel, sel_idx, topk_idx, topk_w);
+}
+
 struct RoutePlan {
     int T16, E16, KS, NT;
 };
@@ -253,6 +346,16 @@ size_t route_workspace_bytes(const moe_config& c) {
 
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
                         int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s) {
+    if (c.E <= 16 && c.T <= 2048) {   // beyond that the MFMA path's higher throughput wins (measured)
+        const dim3 g(c.T);
+        if (c.E <= 8)
+            hipLaunchKernelGGL(route_direct_kernel<8>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d,
+                               c.E, c.k, c.gating);
+        else
+            hipLaunchKernelGGL(route_direct_kernel<16>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d,
+                               c.E, c.k, c.gating);
+        return hipGetLastError();
+    }
     const RoutePlan p = plan(c);
     const int units = p.T16 * ((p.E16 + p.NT - 1) / p.NT) * p.KS;
     double* part = (double*)workspace;
