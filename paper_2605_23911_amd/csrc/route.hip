@@ -16,7 +16,7 @@
 //   one token and eight experts; each unit writes its 16x16 fp64 partial tile.
 // Kernel 2 (gate + top-k): one wavefront per token sums the slices, applies the gate and
 //   selects k experts.
-// Models with at most 16 experts take a single kernel instead (route_direct_kernel).
+// Models with at most 8 experts take a single kernel instead (route_direct_kernel).
 #include "moe_internal.hpp"
 
 namespace moe {
@@ -241,8 +241,8 @@ __global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict
     gate_and_select(z, ok, lane, wave, t, k, gating, wsel, sel_idx, topk_idx, topk_w);
 }
 
-// ---- few experts (E <= 16): the whole router in one kernel, one workgroup per token ----------
-// With 8 or 16 experts a 16x16 MFMA tile would be mostly padding and the two-kernel path costs
+// ---- few experts (E <= 8): the whole router in one kernel, one workgroup per token ----------
+// With 8 experts a 16x16 MFMA tile would be half padding and the two-kernel path costs
 // two launches for a few microseconds of work.  Here thread i takes 8 consecutive k of every
 // 2048, multiplies them with the same k of all E router rows in fp64 (bf16 -> fp64 is exact, so
 // are the products); butterfly sums and one LDS exchange leave the logits in wavefront 0, which
@@ -346,14 +346,10 @@ size_t route_workspace_bytes(const moe_config& c) {
 
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
                         int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s) {
-    if (c.E <= 16 && c.T <= 2048) {   // beyond that the MFMA path's higher throughput wins (measured)
+    if (c.E <= 8 && c.T <= 2048) {   // measured: with 16 experts or more tokens the MFMA path is faster
         const dim3 g(c.T);
-        if (c.E <= 8)
-            hipLaunchKernelGGL(route_direct_kernel<8>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d,
-                               c.E, c.k, c.gating);
-        else
-            hipLaunchKernelGGL(route_direct_kernel<16>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d,
-                               c.E, c.k, c.gating);
+        hipLaunchKernelGGL(route_direct_kernel<8>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d, c.E,
+                           c.k, c.gating);
         return hipGetLastError();
     }
     const RoutePlan p = plan(c);
