@@ -43,7 +43,7 @@ typedef enum {
     MOE_ERR_SHAPE = -2,       /* T<0, k<1, k>E, E<1, d<1, F<1, unknown gating */
     MOE_ERR_ALIGN = -3,       /* a tensor base pointer is not 16-byte aligned */
     MOE_ERR_WORKSPACE = -4,   /* workspace smaller than the matching *_workspace_size() */
-    MOE_ERR_UNSUPPORTED = -5, /* E > 256, d % 64 != 0, F % 64 != 0, sizes beyond 32-bit rows */
+    MOE_ERR_UNSUPPORTED = -5, /* E > 256, d % 64 != 0, F % 64 != 0, T*k > 2^30, or T*k*max(d,F)*2 bytes >= 4 GiB */
     MOE_ERR_HIP = -6          /* a kernel launch reported a HIP error */
 } moe_status;
 

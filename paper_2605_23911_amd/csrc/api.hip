@@ -30,6 +30,9 @@ moe_status check_config(const moe_config* c) {
     if (c->E > kMaxExperts) return MOE_ERR_UNSUPPORTED;
     if (c->d % 64 != 0 || c->F % 64 != 0) return MOE_ERR_UNSUPPORTED;
     if ((long long)c->T * c->k > (1ll << 30)) return MOE_ERR_UNSUPPORTED;
+    // the GEMM kernels address activation rows with 32-bit byte offsets: x, x_perm and h stay below 4 GiB
+    const unsigned long long R = (unsigned long long)c->T * c->k;
+    if (R * (unsigned long long)(c->d > c->F ? c->d : c->F) * 2ull >= (1ull << 32)) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 

@@ -50,6 +50,11 @@ def test_config_validation(L):
     assert st == -2
     assert L.moe_route(C.byref(bad[3]), 16, 16, None, 16, 16, 16, 1 << 20, None) == -5
     assert L.moe_route(C.byref(bad[4]), 16, 16, None, 16, 16, 16, 1 << 20, None) == -5
+    # activation buffers are addressed with 32-bit byte offsets: T*k*max(d,F)*2 must stay below 4 GiB
+    fits = moe.MoEConfig.of(32768, 7168, 2048, 256, 8)          # 262144 rows x 7168 x 2 = 3.5 GiB
+    too_big = moe.MoEConfig.of(40000, 7168, 2048, 256, 8)       # 4.3 GiB
+    assert moe.forward_workspace_size(fits) > 0 and moe.forward_workspace_size(too_big) == 0
+    assert L.moe_route(C.byref(too_big), 16, 16, None, 16, 16, 16, 1 << 20, None) == -5
 
 
 def test_null_alignment_and_workspace_errors_need_no_gpu(L):

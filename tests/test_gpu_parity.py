@@ -159,6 +159,42 @@ def test_degenerate_shapes(G, T, E, k, packed):
     _check_floats(out, ref, layer, G)
 
 
+@pytest.mark.parametrize("T,E", [(300, 8), (2100, 8), (700, 5), (300, 16)])
+def test_router_paths_agree_with_the_oracle(G, T, E):
+    """Few experts and few tokens take the single-kernel router, everything else the fp64-MFMA
+    tiles + top-k kernel: both sides of each switch (E <= 8, T <= 2048), all three gatings."""
+    for gating in (mi.GATE_SOFTMAX, mi.GATE_SOFTMAX_RENORM, mi.GATE_SIGMOID_NORM):
+        s = mi.MoEShape("route", T, 320, 64, E, 2, gating)
+        _say(f"router T={T} E={E} gating={gating}")
+        layer = G.Layer(s, seed=21 + gating, skew=1.0)
+        idx_ref, w_ref, gap = orc.route(layer.x_bits, layer.wr_bits, layer.bias_np, s.k, gating)
+        assert gap.min() > GAP_MIN, "seeded logits too close to certify index parity"
+        idx, w = G.run_route(layer)
+        assert np.array_equal(idx, idx_ref)
+        assert np.abs(w.astype(np.float64) - w_ref).max() <= 1e-6
+
+
+@pytest.mark.parametrize("shape", [("a", 333, 192, 320, 7, 3), ("b", 1500, 256, 384, 4, 2)])
+def test_forward_equals_the_stage_entry_points(G, shape):
+    """moe_forward reads token rows through src_of inside the gate+up kernel; moe_permute +
+    moe_grouped_ffn + moe_combine work on the materialised permuted copy.  Same kernels, same
+    values, same order of summation: the bits of h, y_perm and y must be identical."""
+    s = mi.MoEShape(*shape, mi.GATE_SOFTMAX_RENORM)
+    _say(f"forward vs stages T={s.T} d={s.d} F={s.F} E={s.E} k={s.k}")
+    layer = G.Layer(s, seed=5, skew=1.0)
+    out = G.run_forward(layer)
+    cfg = layer.cfg()
+    idx, w = G.run_route(layer)
+    c, o, ro, so, xp = G.run_permute(cfg, idx, layer.x)
+    h_bits, yp_bits = G.run_ffn(layer, cfg, xp, o)
+    y_bits = G.run_combine(cfg, yp_bits, ro, w)
+    assert np.array_equal(idx, out["topk_idx"]) and np.array_equal(w, out["topk_w"])
+    assert np.array_equal(ro, out["row_of"]) and np.array_equal(so, out["src_of"])
+    assert np.array_equal(h_bits, out["h"])
+    assert np.array_equal(yp_bits, out["y_perm"])
+    assert np.array_equal(y_bits, out["y"])
+
+
 def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
     """The GEMM variants that stage the token tile with LDS-DMA loads (selected by environment
     variable; not the default) against the oracle, and a HIP-graph capture of moe_forward whose
