@@ -21,6 +21,9 @@ const Variant kDown[] = {
     /*12*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true, 4, true>, "tile_kernel<8, 1, false, 4, 2, true, true, 4, true>"},
     /*13*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 4, true>, "tile_kernel<8, 2, false, 2, 1, true, true, 4, true>"},
     /*14*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false, 4, true>, "tile_kernel<8, 1, false, 3, 1, true, false, 4, true>"},
+    /*15*/ {256, true, launch_tile_mixed<1, false, 4, 2, true, true>, "tile_kernel_mixed<1, false, 4, 2, true, true>"},
+    /*16*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, true>, "tile_kernel_mixed<2, false, 2, 1, true, true>"},
+    /*17*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, false>, "tile_kernel_mixed<2, false, 2, 1, true, false>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -40,10 +43,11 @@ int pick(int M, bool packed, const moe_config& c) {
     // non-temporal weight loads while experts are single blocks and the token buffers are small
     const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
     if (!packed) return once ? 14 : 0;
-    if (once) return wide ? 13 : 12;
-    // experts spanning several row tiles: LDS-DMA token tile, two weight blocks per wavefront
-    if ((double)R / c.E > 192.0 && M == 256) return 11;
-    return wide ? 4 : 3;
+    // per-block regime selection (tile_kernel_mixed): experts spanning several row tiles take the
+    // LDS-DMA body; with many rows per expert on average the two-weight-block form of it
+    if (once) return wide ? 16 : 15;
+    if ((double)R / c.E > 192.0 || wide) return 17;
+    return 3;
 }
 
 }  // namespace
@@ -57,7 +61,7 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
-    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), rot_steps(true), wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
     // token rows are addressed with 32-bit byte offsets from the buffer's base
     if ((unsigned long long)a.x_rows * (unsigned long long)ldh * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_dn != nullptr;

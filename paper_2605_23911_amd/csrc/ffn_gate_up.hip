@@ -20,22 +20,21 @@ const Variant kGateUp[] = {
     /*9*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
     /*10*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, true, 4, true>"},
     /*11*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, false, 4, true>"},
+    /*12*/ {256, true, launch_tile_mixed<1, true, 2, 1, true, true>, "tile_kernel_mixed<1, true, 2, 1, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
-// The dynamic-height 256-row kernel serves every schedule (its body follows the rows each block
-// really holds); the others are kept for comparison runs.
-// Non-temporal weight loads while every expert is (nearly always) a single block: each weight
-// byte is then used once per launch (see load_w16).  Measured faster at every such point, also
-// when the token buffer is far larger than L2 (DeepSeek-V3 shape, T=4096: 2.74 -> 2.66 ms).
+// Packed weights: one kernel for every schedule and every routing distribution.  It picks the
+// body per block from the rows the block holds and the regime per block from the rows its expert
+// holds (tile_kernel_mixed).  Row-major weights: the register-staged kernel, with non-temporal
+// weight loads while experts are (on average) single blocks.  The other entries are kept for
+// comparison runs.
 bool stream_once(const moe_config& c) {
     return (double)c.T * c.k / c.E <= 192.0;
 }
 int pick(int M, bool packed, const moe_config& c) {
-    if (stream_once(c)) return packed ? 10 : 11;
-    // experts spanning several row tiles: the LDS-DMA token tile (deeper prefetch, no staging registers)
-    if (packed && (double)c.T * c.k / c.E > 192.0 && M == 256) return 9;
-    return packed ? 3 : 0;
+    if (packed) return 12;
+    return stream_once(c) ? 11 : 0;
 }
 
 }  // namespace
@@ -50,7 +49,7 @@ hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows
                           int32_t ldh, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s) {
-    GemmArgs a{x_rows, src_of, c.k, src_of ? c.T : c.T * c.k, ldx, ldh, rot_steps(false), wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
+    GemmArgs a{x_rows, src_of, c.k, src_of ? c.T : c.T * c.k, ldx, ldh, rot_steps(false), rot_steps(true), wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
     // token rows are addressed with 32-bit byte offsets from the buffer's base
     if ((unsigned long long)a.x_rows * (unsigned long long)ldx * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_gu != nullptr;

@@ -50,6 +50,7 @@ struct GemmArgs {
     int x_rows;                 // rows of X (T with a source map, else R); x_rows * ldx * 2 bytes < 4 GiB
     int ldx, ldo;               // row strides of X and Out in elements (>= K and >= N)
     int rot_mul;                // k-loop rotation between workgroups of one XCD, in steps (see tile_body)
+    int rot_mul_multi;          // the same for blocks of experts that span several row tiles (tile_kernel_mixed)
     const uint16_t* W0;         // [E, N, K]  gate (or down)
     const uint16_t* W1;         // [E, N, K]  up   (unused for down)
     const uint16_t* P;          // packed weights of this projection (PACKED kernels), else unused
@@ -173,6 +174,7 @@ __device__ __forceinline__ uint32_t token_row_bytes(const GemmArgs& a, int row) 
 // Block schedule entry -> tile geometry (Alg. 1: block = (expert, row offset)).
 struct Tile {
     int e, row0, rows;
+    int n_e;   // rows of the whole expert
 };
 __device__ __forceinline__ bool load_tile(const GemmArgs& a, int tile, int BM, Tile& t) {
     BM = a.M < BM ? a.M : BM;   // a kernel may serve a schedule with shorter blocks than it can hold
@@ -183,6 +185,7 @@ __device__ __forceinline__ bool load_tile(const GemmArgs& a, int tile, int BM, T
     const int n_e = a.offsets[t.e + 1] - seg0;
     t.row0 = seg0 + r_in;
     t.rows = (n_e - r_in) < BM ? (n_e - r_in) : BM;
+    t.n_e = n_e;
     return true;
 }
 
@@ -587,6 +590,23 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
 // future work (its Sec. 4.7 and limitation 5): Algorithm 1 runs with M = 256 and the tile
 // height inside a block follows n_e.  Empty token blocks cost neither loads, LDS traffic nor
 // MFMA issue slots.  Pipeline depths per body are what the register file allows.
+// Body of the 256-row dynamic-height kernel for a block of t.rows rows (four wavefronts).
+template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+__device__ __forceinline__ void tile_dispatch(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
+    constexpr int NI = IB * (GATEUP ? 2 : 1);
+    constexpr int SD = NI >= 4 ? 3 : 4;          // stages for the small bodies
+    constexpr int S56 = NI >= 4 ? 2 : SD;
+    switch ((t.rows + 31) / 32) {
+        case 1: return tile_body<8, 1, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        case 2: return tile_body<8, 2, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        case 3: return tile_body<8, 3, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        case 4: return tile_body<8, 4, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        case 5: return tile_body<8, 5, IB, GATEUP, S56, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        case 6: return tile_body<8, 6, IB, GATEUP, S56, 2, PACKED, 4, WNT>(a, t, nt, xs);
+        default: return tile_body<8, 8, IB, GATEUP, STAGES, XD, PACKED, 4, WNT>(a, t, nt, xs);
+    }
+}
+
 template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW, bool WNT>
 __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
@@ -594,17 +614,7 @@ __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
     int tile, nt;
     if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, JB * 32, t)) return;
     if constexpr (DYN && JB == 8 && NW == 4) {
-        constexpr int SD = (IB * (GATEUP ? 2 : 1) >= 4) ? 3 : 4;   // stages for the small bodies
-        const int jbe = (t.rows + 31) / 32;
-        switch (jbe) {
-            case 1: return tile_body<JB, 1, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            case 2: return tile_body<JB, 2, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            case 3: return tile_body<JB, 3, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            case 4: return tile_body<JB, 4, IB, GATEUP, SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            case 5: return tile_body<JB, 5, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            case 6: return tile_body<JB, 6, IB, GATEUP, (IB * (GATEUP ? 2 : 1) >= 4) ? 2 : SD, 2, PACKED, NW, WNT>(a, t, nt, xs);
-            default: break;
-        }
+        return tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
     } else if constexpr (DYN && JB == 8) {
         const int jbe = (t.rows + 31) / 32;
         if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
@@ -616,11 +626,7 @@ __global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
 
 // The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
 template <int IB, bool GATEUP, bool PACKED>
-__global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
-    Tile t;
-    int tile, nt;
-    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
+__device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NI = IB * (GATEUP ? 2 : 1);
     constexpr int SD = NI >= 4 ? 3 : 4;
     switch ((t.rows + 31) / 32) {
@@ -632,6 +638,35 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
         case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
         default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED>(a, t, nt, xs);
     }
+}
+
+template <int IB, bool GATEUP, bool PACKED>
+__global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
+    Tile t;
+    int tile, nt;
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
+    dma_dispatch<IB, GATEUP, PACKED>(a, t, nt, xs);
+}
+
+// The regime is a property of the EXPERT, not of the launch: under routing skew a few experts
+// hold thousands of rows while most hold a handful.  This kernel decides per block.  An expert
+// that fits one block streams its weights once: register-staged token tile, non-temporal weight
+// loads if WNT, k loop rotated against its XCD neighbours.  An expert that spans several row
+// tiles shares its weight panels through L2: LDS-DMA token tile, cached weight loads, k walked
+// in step.  (Packed weights; STAGES / XD are those of the 256-row register-staged body.)
+template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+__global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
+    Tile t;
+    int tile, nt;
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
+    if (t.n_e > a.M) {
+        GemmArgs b = a;
+        b.rot_mul = a.rot_mul_multi;
+        return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
+    }
+    tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
 }
 
 // =============================================================================================
@@ -797,6 +832,25 @@ hipError_t launch_tile_dma(const GemmArgs& a, int max_blocks, hipStream_t s) {
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
     args.rot_mul = rot_steps(true);
+    const long long grid = (long long)max_blocks * args.n_tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
+    return hipGetLastError();
+}
+
+template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
+    constexpr int BN = 4 * IB * 32;
+    constexpr int lds = 4 * 8 * 32 * 128;   // the DMA ring (128 KiB) also holds the two padded register-staged buffers
+    static_assert((size_t)2 * 256 * kLdsStride * sizeof(uint16_t) <= (size_t)lds, "LDS");
+    auto kern = tile_kernel_mixed<IB, GATEUP, STAGES, XD, PACKED, WNT>;
+    // once per process and kernel: not allowed while a stream is being captured into a graph
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    GemmArgs args = a;
+    args.n_tiles_n = (a.N + BN - 1) / BN;
+    args.rot_mul = rot_steps(false);
+    args.rot_mul_multi = rot_steps(true);
     const long long grid = (long long)max_blocks * args.n_tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();

@@ -115,7 +115,11 @@ def test_tile_height_choice(L):
     assert moe.tile_m(moe.MoEConfig.of(4096, 7168, 2048, 256, 8)) == 256
     assert moe.tile_m(moe.MoEConfig.of(4096, 4096, 14336, 8, 2, tile_m=64)) == 64
     c = moe.MoEConfig.of(512, 4096, 14336, 8, 2)
-    assert "tile_kernel<8" in moe.ffn_kernel_name(c, 0, True) and "tile_kernel<8" in moe.ffn_kernel_name(c, 1, False)
+    # packed weights: the kernel that picks body and regime per block; row-major: the register-staged kernel
+    assert moe.ffn_kernel_name(c, 0, True).startswith("tile_kernel_mixed<1, true")
+    assert moe.ffn_kernel_name(c, 1, True).startswith("tile_kernel_mixed<1, false")
+    assert "tile_kernel<8" in moe.ffn_kernel_name(c, 0, False) and "tile_kernel<8" in moe.ffn_kernel_name(c, 1, False)
+    assert moe.ffn_kernel_name(moe.MoEConfig.of(1, 4096, 14336, 8, 2), 1, True).startswith("skinny_kernel")
 
 
 def test_entry_points_refuse_cpu_tensors(L):
