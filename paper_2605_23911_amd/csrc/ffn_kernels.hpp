@@ -427,7 +427,10 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
 // reads apply the same XOR.  The DMA is issued from inline assembly so that the compiler does
 // not serialise every later LDS read behind it; completion is awaited with an explicit
 // s_waitcnt vmcnt(N) before the step's barrier (loads complete in issue order; N = the number
-// of vector-memory loads this wavefront issues after the batch it waits for).
+// of vector-memory loads this wavefront issues after the batch it waits for).  Memory operations
+// the compiler adds on its own (a spill) cannot break the wait: while the awaited DMA is
+// outstanding the N later loads are outstanding too, so the counter is above N; extra operations
+// only lengthen the wait.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr);   // wave-uniform: goes through M0
