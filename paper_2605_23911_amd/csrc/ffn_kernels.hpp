@@ -202,22 +202,33 @@ __device__ __forceinline__ bool map_workgroup(const GemmArgs& a, int& tile, int&
 }
 
 // Epilogue for one 32x32 MFMA block: the lane holds, for token row (j*32 + lane%32), the
-// features q*8 + 4*(lane/32) + 0..3 (q = 0..3) of the block that starts at feature f0.
+// features q*8 + 4*(lane/32) + 0..3 (q = 0..3) of the block that starts at feature f0.  The two
+// lanes of a row (lane and lane^32) swap halves so that each writes two 16-byte pieces (lane/32
+// = 0: features 0..7 and 16..23, lane/32 = 1: 8..15 and 24..31) instead of four 8-byte ones:
+// half as many store instructions and write requests.  Every lane of the wavefront must call
+// this (the swap is a cross-lane operation); `live` masks the stores of rows beyond the tile.
 template <bool GATEUP>
 __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, uint16_t* out_row, int f0, int half,
-                                            int N) {
+                                            int N, bool live) {
+    uint2 pk[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-        const int f = f0 + q * 8 + half * 4;
-        if (f < N) {
-            float o[4];
+        float o[4];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) o[v] = GATEUP ? silu_mul(g[q * 4 + v], u[q * 4 + v]) : g[q * 4 + v];
-            uint2 pk;
-            pk.x = pack2_bf16(o[0], o[1]);
-            pk.y = pack2_bf16(o[2], o[3]);
-            *reinterpret_cast<uint2*>(out_row + f) = pk;
-        }
+        for (int v = 0; v < 4; ++v) o[v] = GATEUP ? silu_mul(g[q * 4 + v], u[q * 4 + v]) : g[q * 4 + v];
+        pk[q].x = pack2_bf16(o[0], o[1]);
+        pk[q].y = pack2_bf16(o[2], o[3]);
+    }
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {   // pair p: groups q = 2p (kept by half 0) and q = 2p + 1 (kept by half 1)
+        const uint2 give = half ? pk[2 * p] : pk[2 * p + 1];
+        uint2 got;
+        got.x = __shfl_xor(give.x, 32, kWave);
+        got.y = __shfl_xor(give.y, 32, kWave);
+        const int f = f0 + (2 * p + half) * 8;
+        const uint4 v = half ? make_uint4(got.x, got.y, pk[2 * p + 1].x, pk[2 * p + 1].y)
+                             : make_uint4(pk[2 * p].x, pk[2 * p].y, got.x, got.y);
+        if (live && f < N) *reinterpret_cast<uint4*>(out_row + f) = v;
     }
 }
 
@@ -410,9 +421,9 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     static_for<IB>([&](auto ib) {
         static_for<JW>([&](auto j) {
             const int tr = (tgrp * JW + j) * 32 + li;
-            if (tr < t.rows)
-                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * a.ldo,
-                                    n0w + ib * 32, half, N);
+            const bool live = tr < t.rows;
+            store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j],
+                                a.Out + (size_t)(t.row0 + (live ? tr : 0)) * a.ldo, n0w + ib * 32, half, N, live);
         });
     });
 }
@@ -580,9 +591,9 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     static_for<IB>([&](auto ib) {
         static_for<JBE>([&](auto j) {
             const int tr = j * 32 + li;
-            if (tr < t.rows)
-                store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j], a.Out + (size_t)(t.row0 + tr) * a.ldo,
-                                    n0w + ib * 32, half, N);
+            const bool live = tr < t.rows;
+            store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j],
+                                a.Out + (size_t)(t.row0 + (live ? tr : 0)) * a.ldo, n0w + ib * 32, half, N, live);
         });
     });
 }
@@ -778,8 +789,9 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
     }
     static_for<JB>([&](auto j) {
         const int tr = j * 32 + li;
-        if (tr < t.rows)
-            store_block<GATEUP>(acc[0][j], acc[GATEUP ? 1 : 0][j], a.Out + (size_t)(t.row0 + tr) * a.ldo, n0w, half, N);
+        const bool live = tr < t.rows;
+        store_block<GATEUP>(acc[0][j], acc[GATEUP ? 1 : 0][j], a.Out + (size_t)(t.row0 + (live ? tr : 0)) * a.ldo, n0w,
+                            half, N, live);
     });
 }
 
