@@ -22,8 +22,14 @@
  *     Eq. 4's "x W" is therefore x times the transpose of the stored matrix.
  *   - Notation: T tokens, d model dim, F expert FFN dim, E experts, k experts per token,
  *     R = T*k expanded rows, n_e rows routed to expert e.
- *   - Limits: 1 <= k <= E <= 256, d % 64 == 0, F % 64 == 0, T >= 0, T*k*max(d,F) < 2^31 rows*cols
- *     addressed with 64-bit offsets.  T == 0 returns MOE_OK and enqueues nothing.
+ *   - Limits: 1 <= k <= E <= 256, d % 64 == 0, F % 64 == 0, T >= 0, T*k <= 2^30, and the
+ *     activation buffers (x, x_perm, h: T*k*max(d,F) elements of 2 bytes) below 4 GiB: the GEMM
+ *     kernels address their rows with 32-bit byte offsets.  Beyond: MOE_ERR_UNSUPPORTED.
+ *     T == 0 returns MOE_OK and enqueues nothing.
+ *   - Stream capture: the calls record kernel launches only and may be captured into a HIP
+ *     graph; replays equal the eager result.  The first use of a GEMM kernel in a process sets
+ *     a function attribute (its LDS size), which HIP does not allow during capture: run the
+ *     call once eagerly with the same configuration before capturing it.
  *   - All argument checks run on the host before anything is enqueued: a call that returns
  *     an error has had no effect on device memory.  Errors are return codes only.
  */

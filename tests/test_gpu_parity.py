@@ -196,9 +196,11 @@ def test_forward_equals_the_stage_entry_points(G, shape):
 
 
 def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
-    """The GEMM variants that stage the token tile with LDS-DMA loads (selected by environment
-    variable; not the default) against the oracle, and a HIP-graph capture of moe_forward whose
-    replays must equal the eager result bit for bit (the library enqueues kernels only)."""
+    """The GEMM kernels that stage EVERY token tile with LDS-DMA loads (selected by environment
+    variable; the default kernel uses that body only for experts spanning several row tiles)
+    against the oracle, and a HIP-graph capture of moe_forward on the default path (one expert
+    with two row tiles, the rest single blocks) whose replays must equal the eager result bit for
+    bit (the library enqueues kernels only)."""
     import paper_2605_23911_amd as moe
     s = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
     layer = G.Layer(s, seed=3, skew=2.0)
