@@ -61,7 +61,7 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
-    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), rot_steps(true), wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), rot_steps(true), 0, wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
     // token rows are addressed with 32-bit byte offsets from the buffer's base
     if ((unsigned long long)a.x_rows * (unsigned long long)ldh * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_dn != nullptr;

@@ -49,7 +49,7 @@ hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows
                           int32_t ldh, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s) {
-    GemmArgs a{x_rows, src_of, c.k, src_of ? c.T : c.T * c.k, ldx, ldh, rot_steps(false), rot_steps(true), wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
+    GemmArgs a{x_rows, src_of, c.k, src_of ? c.T : c.T * c.k, ldx, ldh, rot_steps(false), rot_steps(true), 0, wg, wu, packed_gu, h, offsets, blocks, num_blocks, c.T * c.k, c.F, c.d, 0, M, nullptr};
     // token rows are addressed with 32-bit byte offsets from the buffer's base
     if ((unsigned long long)a.x_rows * (unsigned long long)ldx * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_gu != nullptr;

@@ -51,6 +51,7 @@ struct GemmArgs {
     int ldx, ldo;               // row strides of X and Out in elements (>= K and >= N)
     int rot_mul;                // k-loop rotation between workgroups of one XCD, in steps (see tile_body)
     int rot_mul_multi;          // the same for blocks of experts that span several row tiles (tile_kernel_mixed)
+    int slots;                  // workgroups the chip runs at once (one per CU); 0 = do not split the last round
     const uint16_t* W0;         // [E, N, K]  gate (or down)
     const uint16_t* W1;         // [E, N, K]  up   (unused for down)
     const uint16_t* P;          // packed weights of this projection (PACKED kernels), else unused
@@ -669,18 +670,51 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
 // loads if WNT, k loop rotated against its XCD neighbours.  An expert that spans several row
 // tiles shares its weight panels through L2: LDS-DMA token tile, cached weight loads, k walked
 // in step.  (Packed weights; STAGES / XD are those of the 256-row register-staged body.)
+//
+// Last round (IB = 2 only).  The grid runs in rounds of `slots` workgroups, one per CU.  With
+// two weight blocks per wavefront a projection has few, heavy workgroups (Mixtral shape, down
+// projection at T=2048: 320 = 1.25 rounds); when the last round is at most half full, each of
+// its workgroups is replaced by two that take one 128-feature half each with the IB = 1 body,
+// so the round lasts about half as long and uses twice the CUs.  Only when at most one full
+// round precedes it: with many rounds the workgroups do not end together, there is no common
+// "last round" to shorten, and the less efficient halves cost more than they gain (measured:
+// -10 % at T=2048, +3..5 % at T=4096 and T=8192 without this condition).
 template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
 __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
     Tile t;
     int tile, nt;
-    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
-    if (t.n_e > a.M) {
-        GemmArgs b = a;
-        b.rot_mul = a.rot_mul_multi;
-        return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
+    bool halves = false;
+    if constexpr (IB == 2 && !GATEUP) {
+        int w = blockIdx.x, sub = 0;
+        const int total = *a.num_blocks * a.n_tiles_n;
+        if (a.slots > 0) {
+            const int full = total / a.slots * a.slots, rem = total - full;
+            if (rem > 0 && 2 * rem <= a.slots && full <= a.slots && w >= full) {
+                const int h = w - full;
+                w = full + (h >> 1);
+                sub = h & 1;
+                halves = true;
+            }
+        }
+        if (w >= total) return;
+        tile = w / a.n_tiles_n;
+        nt = w - tile * a.n_tiles_n;
+        if (halves) nt = 2 * nt + sub;   // index of the 128-feature tile the IB = 1 body works on
+    } else {
+        if (!map_workgroup(a, tile, nt)) return;
     }
-    tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
+    if (!load_tile(a, tile, 256, t)) return;
+    GemmArgs b = a;
+    if (t.n_e > a.M) b.rot_mul = a.rot_mul_multi;
+    if constexpr (IB == 2 && !GATEUP) {
+        if (halves) {
+            if (t.n_e > a.M) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
+            return tile_dispatch<1, GATEUP, 4, 2, PACKED, WNT>(b, t, nt, xs);
+        }
+    }
+    if (t.n_e > a.M) return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
+    tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(b, t, nt, xs);
 }
 
 // =============================================================================================
@@ -866,7 +900,19 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     args.n_tiles_n = (a.N + BN - 1) / BN;
     args.rot_mul = rot_steps(false);
     args.rot_mul_multi = rot_steps(true);
-    const long long grid = (long long)max_blocks * args.n_tiles_n;
+    long long grid = (long long)max_blocks * args.n_tiles_n;
+    args.slots = 0;
+    if constexpr (IB == 2 && !GATEUP) {
+        static const int cus = [] {
+            int dev = 0, n = 0;
+            if (std::getenv("MOE_NO_TAIL_SPLIT") != nullptr) return 0;
+            if (hipGetDevice(&dev) != hipSuccess) return 0;
+            if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+            return n;
+        }();
+        args.slots = cus;
+        grid += cus / 2;     // a split last round has up to slots/2 extra workgroups
+    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
 }
