@@ -5,25 +5,20 @@ namespace moe {
 
 namespace {
 
+// See the gate+up table for the template parameters; skinny_kernel<JB, gateup, STAGES, SPLITK, packed>.
 const Variant kDown[] = {
-    /*0*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false>, "tile_kernel<8, 1, false, 3, 1, true, false, 4>"},
+    /*0*/ {256, false, launch_tile<1, false, 3, 1, false, false>, "tile_kernel<1, false, 3, 1, false, false>"},
     /*1*/ {32, false, launch_skinny<1, false, 4, 4, false>, "skinny_kernel<1, false, 4, 4, false>"},
     /*2*/ {64, false, launch_skinny<2, false, 4, 4, false>, "skinny_kernel<2, false, 4, 4, false>"},
-    /*3*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true>, "tile_kernel<8, 1, false, 4, 2, true, true, 4>"},
-    /*4*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true>, "tile_kernel<8, 2, false, 2, 1, true, true, 4>"},
-    /*5*/ {32, true, launch_skinny<1, false, 4, 4, true>, "skinny_kernel<1, false, 4, 4, true>"},
-    /*6*/ {64, true, launch_skinny<2, false, 4, 4, true>, "skinny_kernel<2, false, 4, 4, true>"},
-    /*7*/ {32, true, launch_skinny<1, false, 4, 1, true>, "skinny_kernel<1, false, 4, 1, true>"},
-    /*8*/ {32, true, launch_tile<1, 1, false, 6, 3, false, true>, "tile_kernel<1, 1, false, 6, 3, false, true, 4>"},
-    /*9*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 8>, "tile_kernel<8, 2, false, 2, 1, true, true, 8>"},
-    /*10*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
-    /*11*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
-    /*12*/ {256, true, launch_tile<8, 1, false, 4, 2, true, true, 4, true>, "tile_kernel<8, 1, false, 4, 2, true, true, 4, true>"},
-    /*13*/ {256, true, launch_tile<8, 2, false, 2, 1, true, true, 4, true>, "tile_kernel<8, 2, false, 2, 1, true, true, 4, true>"},
-    /*14*/ {256, false, launch_tile<8, 1, false, 3, 1, true, false, 4, true>, "tile_kernel<8, 1, false, 3, 1, true, false, 4, true>"},
-    /*15*/ {256, true, launch_tile_mixed<1, false, 4, 2, true, true>, "tile_kernel_mixed<1, false, 4, 2, true, true>"},
-    /*16*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, true>, "tile_kernel_mixed<2, false, 2, 1, true, true>"},
-    /*17*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, false>, "tile_kernel_mixed<2, false, 2, 1, true, false>"},
+    /*3*/ {32, true, launch_skinny<1, false, 4, 4, true>, "skinny_kernel<1, false, 4, 4, true>"},
+    /*4*/ {64, true, launch_skinny<2, false, 4, 4, true>, "skinny_kernel<2, false, 4, 4, true>"},
+    /*5*/ {256, true, launch_tile<1, false, 4, 2, true, false>, "tile_kernel<1, false, 4, 2, true, false>"},
+    /*6*/ {256, true, launch_tile<2, false, 2, 1, true, false>, "tile_kernel<2, false, 2, 1, true, false>"},
+    /*7*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
+    /*8*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
+    /*9*/ {256, true, launch_tile_mixed<1, false, 4, 2, true, true>, "tile_kernel_mixed<1, false, 4, 2, true, true>"},
+    /*10*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, true>, "tile_kernel_mixed<2, false, 2, 1, true, true>"},
+    /*11*/ {256, true, launch_tile_mixed<2, false, 2, 1, true, false>, "tile_kernel_mixed<2, false, 2, 1, true, false>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -38,16 +33,16 @@ int pick(int M, bool packed, const moe_config& c) {
     const long long active = c.E < R ? c.E : R;
     const bool few_rows = (long long)(c.d / 128) * active < 256;
     const bool wide = (long long)(c.d / 256) * (active + R / 256) >= 512;
-    if (few_rows && M <= 32) return packed ? 5 : 1;
-    if (few_rows && M <= 64) return packed ? 6 : 2;
+    if (few_rows && M <= 32) return packed ? 3 : 1;
+    if (few_rows && M <= 64) return packed ? 4 : 2;
     // non-temporal weight loads while experts are single blocks and the token buffers are small
     const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
-    if (!packed) return once ? 14 : 0;
+    if (!packed) return 0;   // row-major lines are consumed by four loads each: cached loads only
     // per-block regime selection (tile_kernel_mixed): experts spanning several row tiles take the
     // LDS-DMA body; with many rows per expert on average the two-weight-block form of it
-    if (once) return wide ? 16 : 15;
-    if ((double)R / c.E > 192.0 || wide) return 17;
-    return 3;
+    if (once) return wide ? 10 : 9;
+    if ((double)R / c.E > 192.0 || wide) return 11;
+    return 5;
 }
 
 }  // namespace

@@ -5,36 +5,28 @@ namespace moe {
 
 namespace {
 
-// {tallest block, packed?, launcher, name}.  tile<JB, IB, gateup, STAGES, XD, DYN, packed, NW>,
-// skinny<JB, gateup, STAGES, SPLITK, packed>.
+// {tallest block, packed?, launcher, kernel template instance as rocprofv3 prints it}.
+// tile_kernel<IB, gateup, STAGES, XD, packed, NT weights>, tile_kernel_dma<IB, gateup, packed>,
+// tile_kernel_mixed<IB, gateup, STAGES, XD, packed, NT weights>.
 const Variant kGateUp[] = {
-    /*0*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false>, "tile_kernel<8, 1, true, 2, 1, true, false, 4>"},
-    /*1*/ {32, false, launch_skinny<1, true, 4, 1, false>, "skinny_kernel<1, true, 4, 1, false>"},
-    /*2*/ {64, false, launch_skinny<2, true, 3, 1, false>, "skinny_kernel<2, true, 3, 1, false>"},
-    /*3*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true>, "tile_kernel<8, 1, true, 2, 1, true, true, 4>"},
-    /*4*/ {32, true, launch_skinny<1, true, 4, 1, true>, "skinny_kernel<1, true, 4, 1, true>"},
-    /*5*/ {64, true, launch_skinny<2, true, 3, 1, true>, "skinny_kernel<2, true, 3, 1, true>"},
-    /*6*/ {32, true, launch_tile<1, 1, true, 4, 2, false, true>, "tile_kernel<1, 1, true, 4, 2, false, true, 4>"},
-    /*7*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 8>, "tile_kernel<8, 1, true, 2, 1, true, true, 8>"},
-    /*8*/ {128, true, launch_tile<4, 2, true, 2, 1, false, true>, "tile_kernel<4, 2, true, 2, 1, false, true, 4>"},
-    /*9*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
-    /*10*/ {256, true, launch_tile<8, 1, true, 2, 1, true, true, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, true, 4, true>"},
-    /*11*/ {256, false, launch_tile<8, 1, true, 2, 1, true, false, 4, true>, "tile_kernel<8, 1, true, 2, 1, true, false, 4, true>"},
-    /*12*/ {256, true, launch_tile_mixed<1, true, 2, 1, true, true>, "tile_kernel_mixed<1, true, 2, 1, true, true>"},
+    /*0*/ {256, false, launch_tile<1, true, 2, 1, false, false>, "tile_kernel<1, true, 2, 1, false, false>"},
+    /*1*/ {256, true, launch_tile<1, true, 2, 1, true, false>, "tile_kernel<1, true, 2, 1, true, false>"},
+    /*2*/ {256, true, launch_tile<1, true, 2, 1, true, true>, "tile_kernel<1, true, 2, 1, true, true>"},
+    /*3*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
+    /*4*/ {256, true, launch_tile_mixed<1, true, 2, 1, true, true>, "tile_kernel_mixed<1, true, 2, 1, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
 // Packed weights: one kernel for every schedule and every routing distribution.  It picks the
 // body per block from the rows the block holds and the regime per block from the rows its expert
-// holds (tile_kernel_mixed).  Row-major weights: the register-staged kernel, with non-temporal
-// weight loads while experts are (on average) single blocks.  The other entries are kept for
-// comparison runs.
-bool stream_once(const moe_config& c) {
-    return (double)c.T * c.k / c.E <= 192.0;
-}
+// holds (tile_kernel_mixed).  Row-major weights: the register-staged kernel with cached loads
+// (a row-major 128-byte line is consumed by four load instructions of a lane pair, so the
+// non-temporal hint would drop it between them: measured 1.7x slower).  Entries 1-3 are the two
+// bodies of the default kernel on their own, for comparison runs and tests.
 int pick(int M, bool packed, const moe_config& c) {
-    if (packed) return 12;
-    return stream_once(c) ? 11 : 0;
+    (void)M;
+    (void)c;
+    return packed ? 4 : 0;
 }
 
 }  // namespace

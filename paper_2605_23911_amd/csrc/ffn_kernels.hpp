@@ -20,13 +20,16 @@
 // [matrix][s][lane] x 16 bytes, so that one load instruction reads 1 KiB contiguous and a
 // wavefront streams one contiguous region.  Both layouts are supported by every kernel.
 //
-// Two kernel families share that mapping:
-//   tile_kernel    token tile (32*JB rows) staged in LDS and shared by the four wavefronts;
-//                  for tiles of 64..256 rows (HBM-bound with real MFMA load, or MFMA-bound).
-//   skinny_kernel  <= 64 token rows, token fragments loaded straight from L2 by each
-//                  wavefront: no LDS, no barrier in the reduction loop; optionally the four
-//                  wavefronts split K (down projection of few-expert models, where there are
-//                  too few output rows to fill 256 CUs otherwise).
+// Kernels that share that mapping:
+//   tile_kernel        token tile (up to 256 rows) staged in LDS through registers and shared by
+//                      the four wavefronts; body chosen per block from the rows it holds.
+//   tile_kernel_dma    the same tile brought global -> LDS by DMA into a ring of buffers.
+//   tile_kernel_mixed  per block: tile_kernel's body for experts that fit one block,
+//                      tile_kernel_dma's for experts that span several (the default).
+//   skinny_kernel      <= 64 token rows, token fragments loaded straight from L2 by each
+//                      wavefront: no LDS, no barrier in the reduction loop; the four wavefronts
+//                      split K (down projection of few-expert models at a handful of tokens,
+//                      where there are too few output rows to fill 256 CUs otherwise).
 #pragma once
 
 #include <cstdlib>
@@ -75,10 +78,12 @@ __device__ __forceinline__ void static_for(F&& f) {
     static_for_impl(std::make_integer_sequence<int, N>{}, f);
 }
 
-// Weight loads.  NT: when every expert is a single block each weight byte is used exactly once
-// per launch, and loading it with the non-temporal hint keeps the streamed weights from evicting
-// the re-used token tiles from L2 (+5..10 % at T <= 512).  When an expert spans several row
-// blocks they share the weight panel through L2 and the hint would defeat that.
+// Weight loads.  NT: when an expert is a single block each PACKED weight byte is used exactly
+// once per launch (one load instruction consumes whole 128-byte lines), and loading it with the
+// non-temporal hint keeps the streamed weights from evicting the re-used token tiles from L2
+// (+5..10 % at T <= 512).  When an expert spans several row blocks they share the weight panel
+// through L2 and the hint would defeat that; so it would for row-major weights, where a line is
+// consumed by four load instructions.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <bool NT>
 __device__ __forceinline__ uint4 load_w16(const uint16_t* p) {
@@ -234,32 +239,25 @@ __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, ui
 }
 
 // =============================================================================================
-// tile_kernel: JB*32 token rows in LDS, IB 32-row weight blocks per wavefront and matrix.
-// NW = 4: four wavefronts, each owning its weight rows and ALL token rows of the tile.
-// NW = 8: the token rows are split in two halves; wavefronts w and w+4 own the same weight rows
-//         (both load them: the second load hits L1) and one half of the tokens each.  Half the
-//         accumulators per wavefront -> two wavefronts per SIMD, so one wavefront's load issue,
-//         LDS waits and barrier overlap with the other's MFMAs.
+// tile_body: up to 256 token rows (JBE blocks of 32) staged in LDS through registers and shared
+// by the four wavefronts; each wavefront owns IB 32-row weight blocks per matrix and ALL token
+// rows of the tile.
 // =============================================================================================
-template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, int NW, bool WNT>
+template <int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
 __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NM = GATEUP ? 2 : 1;
     constexpr int NI = IB * NM;
-    constexpr int BM = JB * 32;
+    constexpr int BM = 256;                     // rows one LDS buffer is laid out for
     constexpr int BN = 4 * IB * 32;
-    constexpr int TH = NW / 4;                  // token groups (1 or 2)
-    constexpr int JW = JBE / TH;                // 32-row token blocks per wavefront
-    constexpr int NTHR = NW * kWave;
-    constexpr int XROWS = NTHR / 8;             // token rows staged per pass (8 threads x 16 B per row)
+    constexpr int JW = JBE;                     // 32-row token blocks per wavefront
+    constexpr int XROWS = kThreads / 8;         // token rows staged per pass (8 threads x 16 B per row)
     constexpr int XP = (JBE * 32) / XROWS;      // passes per step
-    static_assert(JBE % TH == 0 && (JBE * 32) % XROWS == 0, "token tile must split evenly");
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave-uniform: scalar register
     const int li = lane & 31, half = lane >> 5;
-    const int wrow = wave & 3, tgrp = wave >> 2;
     const int K = a.K, N = a.N;
     const int KT = K / kBK;
-    const int n0w = nt * BN + wrow * (IB * 32);
+    const int n0w = nt * BN + wave * (IB * 32);
 
     // Weight fragments: scalar block base per (matrix, row block) + one per-lane byte offset.
     // Out-of-range rows of a ragged last feature tile are clamped, their stores masked.
@@ -283,7 +281,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         xo[p] = token_row_bytes(a, t.row0 + (tid >> 3) + XROWS * p) + (uint32_t)(tid & 7) * 16u;
     });
     const int xs_store = (tid >> 3) * kLdsStride + (tid & 7) * 8;
-    const int xs_read = (tgrp * JW * 32 + li) * kLdsStride + half * 8;
+    const int xs_read = li * kLdsStride + half * 8;
 
     f32x16 acc[NI][JW];
     static_for<NI>([&](auto i) {
@@ -421,7 +419,7 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
 
     static_for<IB>([&](auto ib) {
         static_for<JW>([&](auto j) {
-            const int tr = (tgrp * JW + j) * 32 + li;
+            const int tr = j * 32 + li;
             const bool live = tr < t.rows;
             store_block<GATEUP>(acc[ib][j], acc[GATEUP ? IB + ib : ib][j],
                                 a.Out + (size_t)(t.row0 + (live ? tr : 0)) * a.ldo, n0w + ib * 32, half, N, live);
@@ -612,31 +610,23 @@ __device__ __forceinline__ void tile_dispatch(const GemmArgs& a, const Tile& t, 
     constexpr int SD = NI >= 4 ? 3 : 4;          // stages for the small bodies
     constexpr int S56 = NI >= 4 ? 2 : SD;
     switch ((t.rows + 31) / 32) {
-        case 1: return tile_body<8, 1, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        case 2: return tile_body<8, 2, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        case 3: return tile_body<8, 3, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        case 4: return tile_body<8, 4, IB, GATEUP, SD, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        case 5: return tile_body<8, 5, IB, GATEUP, S56, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        case 6: return tile_body<8, 6, IB, GATEUP, S56, 2, PACKED, 4, WNT>(a, t, nt, xs);
-        default: return tile_body<8, 8, IB, GATEUP, STAGES, XD, PACKED, 4, WNT>(a, t, nt, xs);
+        case 1: return tile_body<1, IB, GATEUP, SD, 2, PACKED, WNT>(a, t, nt, xs);
+        case 2: return tile_body<2, IB, GATEUP, SD, 2, PACKED, WNT>(a, t, nt, xs);
+        case 3: return tile_body<3, IB, GATEUP, SD, 2, PACKED, WNT>(a, t, nt, xs);
+        case 4: return tile_body<4, IB, GATEUP, SD, 2, PACKED, WNT>(a, t, nt, xs);
+        case 5: return tile_body<5, IB, GATEUP, S56, 2, PACKED, WNT>(a, t, nt, xs);
+        case 6: return tile_body<6, IB, GATEUP, S56, 2, PACKED, WNT>(a, t, nt, xs);
+        default: return tile_body<8, IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
     }
 }
 
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW, bool WNT>
-__global__ __launch_bounds__(NW* kWave) void tile_kernel(const GemmArgs a) {
+template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+__global__ __launch_bounds__(kThreads) void tile_kernel(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) uint16_t xs[];
     Tile t;
     int tile, nt;
-    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, JB * 32, t)) return;
-    if constexpr (DYN && JB == 8 && NW == 4) {
-        return tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
-    } else if constexpr (DYN && JB == 8) {
-        const int jbe = (t.rows + 31) / 32;
-        if (jbe <= 2) return tile_body<JB, 2, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
-        if (jbe <= 4) return tile_body<JB, 4, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
-        if (jbe <= 6) return tile_body<JB, 6, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
-    }
-    tile_body<JB, JB, IB, GATEUP, STAGES, XD, PACKED, NW, WNT>(a, t, nt, xs);
+    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
+    tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(a, t, nt, xs);
 }
 
 // The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
@@ -845,18 +835,16 @@ inline int rot_steps(bool dma) {
 }
 
 
-template <int JB, int IB, bool GATEUP, int STAGES, int XD, bool DYN, bool PACKED, int NW = 4, bool WNT = false>
+template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
 hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     constexpr int BN = 4 * IB * 32;
-    constexpr size_t lds = (size_t)2 * JB * 32 * kLdsStride * sizeof(uint16_t);
-    auto kern = tile_kernel<JB, IB, GATEUP, STAGES, XD, DYN, PACKED, NW, WNT>;
-    static bool attr_done = false;   // dynamic LDS above 64 KB needs an explicit opt-in, once per process
-    if (!attr_done && lds > 65536) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    constexpr int lds = 2 * 256 * kLdsStride * (int)sizeof(uint16_t);   // two buffers of 256 padded rows: 72 KiB
+    auto kern = tile_kernel<IB, GATEUP, STAGES, XD, PACKED, WNT>;
+    // dynamic LDS above 64 KB needs an explicit opt-in; once per process and kernel (not allowed
+    // while a stream is being captured into a graph)
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
 #ifdef MOE_STEP_TIMING
@@ -865,7 +853,7 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
                    : nullptr;
 #endif
     const long long grid = (long long)max_blocks * args.n_tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NW * kWave), lds, s, args);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
 }
 

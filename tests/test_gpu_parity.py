@@ -205,8 +205,8 @@ def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
     s = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
     layer = G.Layer(s, seed=3, skew=2.0)
     ref = _oracle_full(layer)
-    monkeypatch.setenv("MOE_GU_VARIANT", "9")
-    monkeypatch.setenv("MOE_DN_VARIANT", "10")
+    monkeypatch.setenv("MOE_GU_VARIANT", "3")
+    monkeypatch.setenv("MOE_DN_VARIANT", "7")
     cfg = layer.cfg()
     assert "dma" in moe.ffn_kernel_name(cfg, 0, True) and "dma" in moe.ffn_kernel_name(cfg, 1, True)
     _say("LDS-DMA variants on the ragged shape")
