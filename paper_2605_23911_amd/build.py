@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_NAME = "libmoe_mi355x.so"
 LIB_PATH = os.path.join(PKG_DIR, LIB_NAME)
-SOURCES = ["ffn_gate_up.hip", "ffn_down.hip", "api.hip", "route.hip", "permute.hip", "pack.hip", "combine.hip"]
+SOURCES = ["ffn_down_wide.hip", "ffn_gate_up.hip", "ffn_down.hip", "api.hip", "route.hip", "permute.hip", "pack.hip", "combine.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -39,7 +39,7 @@ def _run(cmd, verbose):
         print(err, file=sys.stderr)
 
 
-def build_library(verbose: bool = False, extra_flags=(), jobs: int = 4) -> str:
+def build_library(verbose: bool = False, extra_flags=(), jobs: int = 8) -> str:
     """Compile every translation unit (in parallel) and link them into the shared library."""
     from concurrent.futures import ThreadPoolExecutor
     objdir = os.path.join(PKG_DIR, "_build")

@@ -40,12 +40,6 @@
 
 namespace moe {
 
-namespace {
-
-constexpr int kThreads = 256;
-constexpr int kBK = 64;            // reduction elements per pipeline step
-constexpr int kLdsStride = 72;     // bf16 elements per staged token row: 64 + 8 pad (144 B)
-
 struct GemmArgs {
     const uint16_t* X;          // [R, K] expert-contiguous rows, or the un-permuted [T, K] rows if src != nullptr
     const int32_t* src;         // [R] flat (token, slot) index of every expert-contiguous row, or nullptr
@@ -66,6 +60,20 @@ struct GemmArgs {
     int M;                      // tile height of the block schedule (rows per block <= M)
     unsigned long long* dbg;   // MOE_STEP_TIMING builds only
 };
+
+typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
+
+// The down projection's per-block-regime kernels with two weight blocks per wavefront are
+// compiled in a translation unit of their own (ffn_down_wide.hip) to shorten the build.
+hipError_t launch_down_mixed_wide_nt(const GemmArgs& a, int max_blocks, hipStream_t s);
+hipError_t launch_down_mixed_wide(const GemmArgs& a, int max_blocks, hipStream_t s);
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kBK = 64;            // reduction elements per pipeline step
+constexpr int kLdsStride = 72;     // bf16 elements per staged token row: 64 + 8 pad (144 B)
+
 
 template <int... Is, class F>
 __device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F&& f) {
@@ -822,8 +830,6 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
 // =============================================================================================
 // launch helpers
 // =============================================================================================
-typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
-
 // k-loop rotation between the workgroups of an XCD, in steps.  Single-block experts (weights
 // streamed once): 2, which spreads the row-strided token tile reads over the L2 channels.
 // Multi-tile experts (the LDS-DMA kernels): 0, so that row tiles that share a weight panel, and
