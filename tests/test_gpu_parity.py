@@ -320,3 +320,17 @@ def test_qwen2moe_T512_skewed(G):
 
 def test_dsv3_T512(G):
     _sampled_full_size(G, "dsv3", 512, 3)
+
+
+def test_mixtral_T1_decode(G):
+    _sampled_full_size(G, "mixtral", 1, 1)
+
+
+def test_qwen2moe_T4096(G):
+    _sampled_full_size(G, "qwen2moe", 4096, 4)
+
+
+def test_dsv3_T4096_skewed(G):
+    """Skew 1 at the largest shape: a few experts hold thousands of rows (sixteen 256-row tiles,
+    LDS-DMA body), most a handful (register-staged body), all in one launch."""
+    _sampled_full_size(G, "dsv3", 4096, 3, skew=1.0)
