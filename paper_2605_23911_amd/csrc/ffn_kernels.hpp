@@ -372,19 +372,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
         MOE_TICK(0)
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
-                wreg[wst][i][s] = w_load(i, kw, s);
-                if constexpr (i == 0 && s < 3) {
-                    static_for<JW>([&](auto j) {
-                        xf[(s + 1) & 1][j] = *reinterpret_cast<const bf16x8*>(
-                            &xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride + (s + 1) * 16]);
-                    });
-                }
-                __builtin_amdgcn_sched_barrier(0);
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
                 static_for<JW>([&](auto j) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[s & 1][j], acc[i][j], 0, 0, 0);
+                    constexpr int p = i * JW + j;   // position in the slot: one memory instruction behind each MFMA
+                    if constexpr (j == 0) wreg[wst][i][s] = w_load(i, kw, s);
+                    if constexpr (s < 3 && p % NI == NI - 1) {
+                        constexpr int jj = p / NI;
+                        xf[(s + 1) & 1][jj] = *reinterpret_cast<const bf16x8*>(
+                            &xs[buf * BM * kLdsStride + xs_read + jj * 32 * kLdsStride + (s + 1) * 16]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 });
-                __builtin_amdgcn_sched_barrier(0);
             });
         });
         MOE_TICK(1)
