@@ -59,6 +59,7 @@ struct GemmArgs {
     int R, N, K, n_tiles_n;
     int M;                      // tile height of the block schedule (rows per block <= M)
     unsigned long long* dbg;   // MOE_STEP_TIMING builds only
+    int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
 };
 
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
@@ -708,6 +709,41 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     } else {
         if (!map_workgroup(a, tile, nt)) return;
     }
+    // Row tiles of one expert side by side.  The workgroups of an expert with n row tiles are a
+    // contiguous span of n * n_tiles_n ids that starts at a multiple of 8, so id % 8 (the XCD the
+    // hardware deals the workgroup to) is a property of the position in the span.  In plain
+    // tile-major order the n workgroups that read the same weight panel are n_tiles_n ids apart:
+    // they start microseconds apart, and an XCD's 4 MiB of L2 hold only about three k steps of
+    // its 32 workgroups' streams, so each of them fetches the panel from beyond L2 for itself.
+    // Inside the span the order is therefore (feature tile, row tile) per XCD: the n row tiles of
+    // a panel are consecutive workgroups of one XCD, start together and walk k in step.  A short
+    // last tile (a different, faster body) would not stay in step anyway: those go to the end of
+    // the span.  The XCD of every (expert, feature tile) pair is the same as in tile-major order.
+    // (Mixtral shape, T=4096: layer -3 %; T=8192 -2 %; no effect on single-tile experts.)
+    if (a.sib && !halves && (a.n_tiles_n & 7) == 0 && tile < *a.num_blocks) {
+        const int e = a.blocks[2 * tile], r_in = a.blocks[2 * tile + 1];
+        const int n_e = a.offsets[e + 1] - a.offsets[e];
+        const int bm = a.M < 256 ? a.M : 256;
+        const int n = (n_e + bm - 1) / bm;             // row tiles of this expert
+        if (n >= 2) {
+            auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 6 ? 7 : c; };
+            const int base = tile - r_in / bm;         // the expert's first schedule entry
+            const int nt8 = a.n_tiles_n >> 3;
+            const int l = (tile - base) * a.n_tiles_n + nt;   // index inside the expert's span of workgroups
+            const int x = l & 7, m = l >> 3;           // the span starts at a multiple of 8: x is the XCD
+            const int nf = body(n_e - (n - 1) * bm) == body(bm) ? n : n - 1;   // tiles that run the full-height body
+            int tl, ntl;
+            if (m < nf * nt8) {
+                ntl = m / nf;
+                tl = m - ntl * nf;
+            } else {
+                tl = n - 1;
+                ntl = m - nf * nt8;
+            }
+            tile = base + tl;
+            nt = ntl * 8 + x;
+        }
+    }
     if (!load_tile(a, tile, 256, t)) return;
     GemmArgs b = a;
     if (t.n_e > a.M) b.rot_mul = a.rot_mul_multi;
@@ -899,6 +935,10 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
     args.rot_mul = rot_steps(false);
+    {   // development hook: MOE_SIB=0 keeps the plain tile-major order
+        const char* e_ = std::getenv("MOE_SIB");
+        args.sib = e_ != nullptr ? std::atoi(e_) : 1;
+    }
     args.rot_mul_multi = rot_steps(true);
     long long grid = (long long)max_blocks * args.n_tiles_n;
     args.slots = 0;
