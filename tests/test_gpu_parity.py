@@ -195,6 +195,28 @@ def test_forward_equals_the_stage_entry_points(G, shape):
     assert np.array_equal(y_bits, out["y"])
 
 
+def test_row_tiles_of_an_expert_side_by_side(G, monkeypatch):
+    """Experts of three row tiles (two full, one short) on shapes whose feature-tile counts are
+    multiples of 8, so that the default kernels re-order the workgroups inside each expert's span
+    (row tiles that share a weight panel next to each other on one XCD): every element against the
+    oracle, and bit-equal to the plain tile-major order (same tiles, same arithmetic, different
+    workgroup ids)."""
+    s = mi.MoEShape("three_tiles", 900, 2048, 2048, 3, 2, mi.GATE_SOFTMAX)
+    layer = G.Layer(s, seed=11, skew=0.5)
+    ref = _oracle_full(layer)
+    assert (ref["counts"] > 512).any() and (ref["counts"] % 256 != 0).all()
+    _say("three-tile experts, side-by-side launch order")
+    out = G.run_forward(layer)
+    _check_routing(out, ref, layer)
+    _check_floats(out, ref, layer, G)
+    monkeypatch.setenv("MOE_SIB", "0")
+    _say("three-tile experts, tile-major launch order")
+    plain = G.run_forward(layer)
+    monkeypatch.delenv("MOE_SIB")
+    for name in ("h", "y_perm", "y"):
+        assert np.array_equal(out[name], plain[name]), name
+
+
 def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
     """The GEMM kernels that stage EVERY token tile with LDS-DMA loads (selected by environment
     variable; the default kernel uses that body only for experts spanning several row tiles)
