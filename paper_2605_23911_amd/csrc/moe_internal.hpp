@@ -27,8 +27,12 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
     return __builtin_bit_cast(uint16_t, h);
 }
 
+// two floats -> two bf16 in one register, lo in bits 15:0 (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-    return (uint32_t)float_to_bf16_bits(lo) | ((uint32_t)float_to_bf16_bits(hi) << 16);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // ---- launchers (each enqueues on `s` and returns hipGetLastError()) ----------------------
