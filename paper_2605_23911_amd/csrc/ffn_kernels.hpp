@@ -722,16 +722,21 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     // last tile (a different, faster body) would not stay in step anyway: those go to the end of
     // the span.  The XCD of every (expert, feature tile) pair is the same as in tile-major order.
     // (Mixtral shape, T=4096: layer -3 %; T=8192 -2 %; no effect on single-tile experts.)
-    if (a.sib && !halves && (a.n_tiles_n & 7) == 0 && tile < *a.num_blocks) {
-        const int e = a.blocks[2 * tile], r_in = a.blocks[2 * tile + 1];
-        const int n_e = a.offsets[e + 1] - a.offsets[e];
-        const int bm = a.M < 256 ? a.M : 256;
+    // The schedule entry is read once: the look-ups (block count, entry, expert offsets, for
+    // the gate+up projection the source row) are dependent loads in front of the block's first
+    // weight and tile loads, each worth several hundred nanoseconds of a ~100 us block.
+    if (tile >= *a.num_blocks) return;
+    const int bm = a.M < 256 ? a.M : 256;              // rows per schedule entry
+    const int e = a.blocks[2 * tile];
+    int r_in = a.blocks[2 * tile + 1];
+    const int seg0 = a.offsets[e];
+    const int n_e = a.offsets[e + 1] - seg0;
+    if (a.sib && !halves && (a.n_tiles_n & 7) == 0) {
         const int n = (n_e + bm - 1) / bm;             // row tiles of this expert
         if (n >= 2) {
             auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 6 ? 7 : c; };
-            const int base = tile - r_in / bm;         // the expert's first schedule entry
             const int nt8 = a.n_tiles_n >> 3;
-            const int l = (tile - base) * a.n_tiles_n + nt;   // index inside the expert's span of workgroups
+            const int l = (r_in / bm) * a.n_tiles_n + nt;     // index inside the expert's span of workgroups
             const int x = l & 7, m = l >> 3;           // the span starts at a multiple of 8: x is the XCD
             const int nf = body(n_e - (n - 1) * bm) == body(bm) ? n : n - 1;   // tiles that run the full-height body
             int tl, ntl;
@@ -742,11 +747,14 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
                 tl = n - 1;
                 ntl = m - nf * nt8;
             }
-            tile = base + tl;
+            r_in = tl * bm;
             nt = ntl * 8 + x;
         }
     }
-    if (!load_tile(a, tile, 256, t)) return;
+    t.e = e;
+    t.row0 = seg0 + r_in;
+    t.rows = (n_e - r_in) < bm ? (n_e - r_in) : bm;
+    t.n_e = n_e;
     GemmArgs b = a;
     if (t.n_e > a.M) b.rot_mul = a.rot_mul_multi;
     if constexpr (IB == 2 && !GATEUP) {
