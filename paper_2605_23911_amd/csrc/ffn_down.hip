@@ -16,9 +16,9 @@ const Variant kDown[] = {
     /*6*/ {256, true, launch_tile<2, false, 2, 1, true, false>, "tile_kernel<2, false, 2, 1, true, false>"},
     /*7*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
     /*8*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
-    /*9*/ {256, true, launch_tile_mixed<1, false, 4, 2, true, true>, "tile_kernel_mixed<1, false, 4, 2, true, true>"},
-    /*10*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, 2, 1, true, true>"},
-    /*11*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, 2, 1, true, false>"},
+    /*9*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true>"},
+    /*10*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true>"},
+    /*11*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 

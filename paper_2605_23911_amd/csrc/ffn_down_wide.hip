@@ -6,11 +6,11 @@
 namespace moe {
 
 hipError_t launch_down_mixed_wide_nt(const GemmArgs& a, int max_blocks, hipStream_t s) {
-    return launch_tile_mixed<2, false, 2, 1, true, true>(a, max_blocks, s);
+    return launch_tile_mixed<2, false, true, true>(a, max_blocks, s);
 }
 
 hipError_t launch_down_mixed_wide(const GemmArgs& a, int max_blocks, hipStream_t s) {
-    return launch_tile_mixed<2, false, 2, 1, true, false>(a, max_blocks, s);
+    return launch_tile_mixed<2, false, true, false>(a, max_blocks, s);
 }
 
 }  // namespace moe

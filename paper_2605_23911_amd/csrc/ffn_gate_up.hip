@@ -7,13 +7,13 @@ namespace {
 
 // {tallest block, packed?, launcher, kernel template instance as rocprofv3 prints it}.
 // tile_kernel<IB, gateup, STAGES, XD, packed, NT weights>, tile_kernel_dma<IB, gateup, packed>,
-// tile_kernel_mixed<IB, gateup, STAGES, XD, packed, NT weights>.
+// tile_kernel_mixed<IB, gateup, packed, NT weights for single-block experts>.
 const Variant kGateUp[] = {
     /*0*/ {256, false, launch_tile<1, true, 2, 1, false, false>, "tile_kernel<1, true, 2, 1, false, false>"},
     /*1*/ {256, true, launch_tile<1, true, 2, 1, true, false>, "tile_kernel<1, true, 2, 1, true, false>"},
     /*2*/ {256, true, launch_tile<1, true, 2, 1, true, true>, "tile_kernel<1, true, 2, 1, true, true>"},
     /*3*/ {256, true, launch_tile_dma<1, true, true>, "tile_kernel_dma<1, true, true>"},
-    /*4*/ {256, true, launch_tile_mixed<1, true, 2, 1, true, true>, "tile_kernel_mixed<1, true, 2, 1, true, true>"},
+    /*4*/ {256, true, launch_tile_mixed<1, true, true, true>, "tile_kernel_mixed<1, true, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
@@ -21,8 +21,9 @@ constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 // body per block from the rows the block holds and the regime per block from the rows its expert
 // holds (tile_kernel_mixed).  Row-major weights: the register-staged kernel with cached loads
 // (a row-major 128-byte line is consumed by four load instructions of a lane pair, so the
-// non-temporal hint would drop it between them: measured 1.7x slower).  Entries 1-3 are the two
-// bodies of the default kernel on their own, for comparison runs and tests.
+// non-temporal hint would drop it between them: measured 1.7x slower).  Entries 1-3 are the
+// register-staged kernel on packed weights and the LDS-DMA body without the per-block regime,
+// for comparison runs and tests.
 int pick(int M, bool packed, const moe_config& c) {
     (void)M;
     (void)c;

@@ -24,8 +24,10 @@
 //   tile_kernel        token tile (up to 256 rows) staged in LDS through registers and shared by
 //                      the four wavefronts; body chosen per block from the rows it holds.
 //   tile_kernel_dma    the same tile brought global -> LDS by DMA into a ring of buffers.
-//   tile_kernel_mixed  per block: tile_kernel's body for experts that fit one block,
-//                      tile_kernel_dma's for experts that span several (the default).
+//   tile_kernel_mixed  tile_kernel_dma's body with the regime chosen per block: weights streamed
+//                      once (non-temporal, k rotated) for experts that fit one block, shared
+//                      through L2 (cached, k in step, row tiles side by side) for experts that
+//                      span several (the default for packed weights).
 //   skinny_kernel      <= 64 token rows, token fragments loaded straight from L2 by each
 //                      wavefront: no LDS, no barrier in the reduction loop; the four wavefronts
 //                      split K (down projection of few-expert models at a handful of tokens,
@@ -647,18 +649,18 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const GemmArgs a) {
 }
 
 // The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
-template <int IB, bool GATEUP, bool PACKED>
+template <int IB, bool GATEUP, bool PACKED, bool WNT = false>
 __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NI = IB * (GATEUP ? 2 : 1);
     constexpr int SD = NI >= 4 ? 3 : 4;
     switch ((t.rows + 31) / 32) {
-        case 1: return tile_body_dma<8, 1, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
-        case 2: return tile_body_dma<8, 2, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
-        case 3: return tile_body_dma<8, 3, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
-        case 4: return tile_body_dma<8, 4, IB, GATEUP, SD, 3, PACKED>(a, t, nt, xs);
-        case 5: return tile_body_dma<8, 5, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
-        case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED>(a, t, nt, xs);
-        default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED>(a, t, nt, xs);
+        case 1: return tile_body_dma<8, 1, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 2: return tile_body_dma<8, 2, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 3: return tile_body_dma<8, 3, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 4: return tile_body_dma<8, 4, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 5: return tile_body_dma<8, 5, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED, WNT>(a, t, nt, xs);
+        default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
     }
 }
 
@@ -672,11 +674,15 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
 }
 
 // The regime is a property of the EXPERT, not of the launch: under routing skew a few experts
-// hold thousands of rows while most hold a handful.  This kernel decides per block.  An expert
-// that fits one block streams its weights once: register-staged token tile, non-temporal weight
-// loads if WNT, k loop rotated against its XCD neighbours.  An expert that spans several row
-// tiles shares its weight panels through L2: LDS-DMA token tile, cached weight loads, k walked
-// in step.  (Packed weights; STAGES / XD are those of the 256-row register-staged body.)
+// hold thousands of rows while most hold a handful.  This kernel decides per block; both regimes
+// run the LDS-DMA body.  An expert that fits one block streams its weights once: non-temporal
+// weight loads if WNT, k loop rotated against its XCD neighbours.  An expert that spans several
+// row tiles shares its weight panels through L2: cached weight loads, k walked in step, its row
+// tiles launched side by side.  (Packed weights.  The register-staged body of tile_kernel was the
+// single-block choice until the memory instructions of the DMA body were dealt singly between
+// its MFMAs; since then the DMA body wins there too: no staging registers, no ds_write, half the
+// instructions per token-tile byte.  Mixtral shape: T=512 layer -6 %, T=1024 -5 %, T <= 256 and
+// the 64- and 256-expert shapes unchanged.)
 //
 // Last round (IB = 2 only).  The grid runs in rounds of `slots` workgroups, one per CU.  With
 // two weight blocks per wavefront a projection has few, heavy workgroups (Mixtral shape, down
@@ -686,7 +692,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
 // round precedes it: with many rounds the workgroups do not end together, there is no common
 // "last round" to shorten, and the less efficient halves cost more than they gain (measured:
 // -10 % at T=2048, +3..5 % at T=4096 and T=8192 without this condition).
-template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+template <int IB, bool GATEUP, bool PACKED, bool WNT>
 __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
     Tile t;
@@ -760,11 +766,11 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     if constexpr (IB == 2 && !GATEUP) {
         if (halves) {
             if (t.n_e > a.M) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
-            return tile_dispatch<1, GATEUP, 4, 2, PACKED, WNT>(b, t, nt, xs);
+            return dma_dispatch<1, GATEUP, PACKED, WNT>(b, t, nt, xs);
         }
     }
     if (t.n_e > a.M) return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
-    tile_dispatch<IB, GATEUP, STAGES, XD, PACKED, WNT>(b, t, nt, xs);
+    dma_dispatch<IB, GATEUP, PACKED, WNT>(b, t, nt, xs);
 }
 
 // =============================================================================================
@@ -932,12 +938,11 @@ hipError_t launch_tile_dma(const GemmArgs& a, int max_blocks, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT>
+template <int IB, bool GATEUP, bool PACKED, bool WNT>
 hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     constexpr int BN = 4 * IB * 32;
-    constexpr int lds = 4 * 8 * 32 * 128;   // the DMA ring (128 KiB) also holds the two padded register-staged buffers
-    static_assert((size_t)2 * 256 * kLdsStride * sizeof(uint16_t) <= (size_t)lds, "LDS");
-    auto kern = tile_kernel_mixed<IB, GATEUP, STAGES, XD, PACKED, WNT>;
+    constexpr int lds = 4 * 8 * 32 * 128;   // the DMA ring: XD+1 = 4 buffers of 256 rows x 128 bytes
+    auto kern = tile_kernel_mixed<IB, GATEUP, PACKED, WNT>;
     // once per process and kernel: not allowed while a stream is being captured into a graph
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);
