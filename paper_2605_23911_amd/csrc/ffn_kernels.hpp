@@ -681,7 +681,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
 // tiles launched side by side.  (Packed weights.  The register-staged body of tile_kernel was the
 // single-block choice until the memory instructions of the DMA body were dealt singly between
 // its MFMAs; since then the DMA body wins there too: no staging registers, no ds_write, half the
-// instructions per token-tile byte.  Mixtral shape: T=512 layer -6 %, T=1024 -5 %, T <= 256 and
+// instructions per token-tile byte.  Mixtral shape: T=512 layer -3 %, T=1024 -5 %, T <= 256 and
 // the 64- and 256-expert shapes unchanged.)
 //
 // Last round (IB = 2 only).  The grid runs in rounds of `slots` workgroups, one per CU.  With
