@@ -62,6 +62,7 @@ struct GemmArgs {
     int M;                      // tile height of the block schedule (rows per block <= M)
     unsigned long long* dbg;   // MOE_STEP_TIMING builds only
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
+    int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
 };
 
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
@@ -697,25 +698,39 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
     Tile t;
     int tile, nt;
-    bool halves = false;
-    if constexpr (IB == 2 && !GATEUP) {
+    bool halves = false, chunked = false;
+    {
         int w = blockIdx.x, sub = 0;
         const int total = *a.num_blocks * a.n_tiles_n;
-        if (a.slots > 0) {
-            const int full = total / a.slots * a.slots, rem = total - full;
-            if (rem > 0 && 2 * rem <= a.slots && full <= a.slots && w >= full) {
-                const int h = w - full;
-                w = full + (h >> 1);
-                sub = h & 1;
-                halves = true;
+        bool split_round = false;
+        if constexpr (IB == 2 && !GATEUP) {
+            if (a.slots > 0) {
+                const int full = total / a.slots * a.slots, rem = total - full;
+                split_round = rem > 0 && 2 * rem <= a.slots && full <= a.slots;
+                if (split_round && w >= full) {
+                    const int h = w - full;
+                    w = full + (h >> 1);
+                    sub = h & 1;
+                    halves = true;
+                }
             }
+        }
+        // One contiguous eighth of the (tile-major) work per XCD: the hardware deals workgroup id
+        // to XCD id % 8, so XCD x takes ids x*per .. x*per+per-1.  All feature tiles of a block
+        // then run on one XCD and its token tile is fetched into one L2 instead of eight (down
+        // projection, single-block experts: the h tile of an expert is read by d/128 workgroups
+        // and makes up half of what a CU loads).
+        if (a.chunk && !split_round) {
+            const int per = (total + 7) >> 3;
+            const int q = w >> 3;
+            if (q >= per) return;
+            w = (w & 7) * per + q;
+            chunked = true;
         }
         if (w >= total) return;
         tile = w / a.n_tiles_n;
         nt = w - tile * a.n_tiles_n;
         if (halves) nt = 2 * nt + sub;   // index of the 128-feature tile the IB = 1 body works on
-    } else {
-        if (!map_workgroup(a, tile, nt)) return;
     }
     // Row tiles of one expert side by side.  The workgroups of an expert with n row tiles are a
     // contiguous span of n * n_tiles_n ids that starts at a multiple of 8, so id % 8 (the XCD the
@@ -737,7 +752,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     int r_in = a.blocks[2 * tile + 1];
     const int seg0 = a.offsets[e];
     const int n_e = a.offsets[e + 1] - seg0;
-    if (a.sib && !halves && (a.n_tiles_n & 7) == 0) {
+    if (a.sib && !halves && !chunked && (a.n_tiles_n & 7) == 0) {
         const int n = (n_e + bm - 1) / bm;             // row tiles of this expert
         if (n >= 2) {
             auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 6 ? 7 : c; };
@@ -954,8 +969,12 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
         const char* e_ = std::getenv("MOE_SIB");
         args.sib = e_ != nullptr ? std::atoi(e_) : 1;
     }
+    {   // development hook: MOE_CHUNK=0/1 overrides the per-XCD chunking (default: down projection with single-use weights)
+        const char* e_ = std::getenv("MOE_CHUNK");
+        args.chunk = e_ != nullptr ? std::atoi(e_) : (!GATEUP && WNT ? 1 : 0);
+    }
     args.rot_mul_multi = rot_steps(true);
-    long long grid = (long long)max_blocks * args.n_tiles_n;
+    long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking
     args.slots = 0;
     if constexpr (IB == 2 && !GATEUP) {
         static const int cus = [] {
