@@ -63,6 +63,7 @@ struct GemmArgs {
     unsigned long long* dbg;   // MOE_STEP_TIMING builds only
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
     int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
+    int even;                   // tile_kernel_mixed: rows of a multi-tile expert dealt evenly over its schedule entries
 };
 
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
@@ -661,6 +662,7 @@ __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, i
         case 4: return tile_body_dma<8, 4, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
         case 5: return tile_body_dma<8, 5, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED, WNT>(a, t, nt, xs);
         case 6: return tile_body_dma<8, 6, IB, GATEUP, NI >= 4 ? 2 : SD, 3, PACKED, WNT>(a, t, nt, xs);
+        case 7: return tile_body_dma<8, 7, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
         default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
     }
 }
@@ -699,9 +701,9 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     Tile t;
     int tile, nt;
     bool halves = false, chunked = false;
+    const int total = *a.num_blocks * a.n_tiles_n;
     {
         int w = blockIdx.x, sub = 0;
-        const int total = *a.num_blocks * a.n_tiles_n;
         bool split_round = false;
         if constexpr (IB == 2 && !GATEUP) {
             if (a.slots > 0) {
@@ -749,32 +751,56 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     if (tile >= *a.num_blocks) return;
     const int bm = a.M < 256 ? a.M : 256;              // rows per schedule entry
     const int e = a.blocks[2 * tile];
-    int r_in = a.blocks[2 * tile + 1];
+    const int r_in = a.blocks[2 * tile + 1];
     const int seg0 = a.offsets[e];
     const int n_e = a.offsets[e + 1] - seg0;
-    if (a.sib && !halves && !chunked && (a.n_tiles_n & 7) == 0) {
-        const int n = (n_e + bm - 1) / bm;             // row tiles of this expert
-        if (n >= 2) {
-            auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 6 ? 7 : c; };
-            const int nt8 = a.n_tiles_n >> 3;
-            const int l = (r_in / bm) * a.n_tiles_n + nt;     // index inside the expert's span of workgroups
-            const int x = l & 7, m = l >> 3;           // the span starts at a multiple of 8: x is the XCD
-            const int nf = body(n_e - (n - 1) * bm) == body(bm) ? n : n - 1;   // tiles that run the full-height body
-            int tl, ntl;
-            if (m < nf * nt8) {
-                ntl = m / nf;
-                tl = m - ntl * nf;
-            } else {
-                tl = n - 1;
-                ntl = m - nf * nt8;
-            }
-            r_in = tl * bm;
-            nt = ntl * 8 + x;
+    const int n = (n_e + bm - 1) / bm;                 // row tiles (schedule entries) of this expert
+    int ti = r_in / bm;                                // which of them this workgroup is
+    // see below; a.even: 0 never, 1 experts of up to three row tiles, 2 those while the launch is at most two rounds, 3 always
+    const bool even = a.even == 3 || (n <= 3 && (a.even == 1 || (a.even == 2 && total <= 2 * a.slots)));
+    if (a.sib && !halves && !chunked && (a.n_tiles_n & 7) == 0 && n >= 2) {
+        auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 7 ? 8 : c; };
+        const int nt8 = a.n_tiles_n >> 3;
+        const int l = ti * a.n_tiles_n + nt;           // index inside the expert's span of workgroups
+        const int x = l & 7, m = l >> 3;               // the span starts at a multiple of 8: x is the XCD
+        // tiles that run the same body as the first one (all of them when the rows are dealt evenly)
+        const int nf = (even || body(n_e - (n - 1) * bm) == body(bm)) ? n : n - 1;
+        int ntl;
+        if (m < nf * nt8) {
+            ntl = m / nf;
+            ti = m - ntl * nf;
+        } else {
+            ti = n - 1;
+            ntl = m - nf * nt8;
         }
+        nt = ntl * 8 + x;
     }
+    // Rows of a multi-tile expert dealt evenly over its n schedule entries, in whole 32-row blocks:
+    // Algorithm 1 gives 1040 rows as 4 x 256 + 16, and the 16-row tile streams a whole weight
+    // panel for 1/16 of the MFMA work, eight times faster through k than its siblings, so it
+    // shares nothing with them (1040 instead of 1024 rows per expert cost +8 % on gate+up and
+    // +15 % on the down projection).  5 x 224 (4 x 224 + 144) is the same number of 32-row MFMA
+    // blocks, ceil(n_e / 32), in tiles that run at about the same pace.  Which rows a workgroup
+    // computes does not change any row's result.  The CU time of the two divisions is about the
+    // same (a 16-row tile costs a third of a full one); what differs is how the launch ends.
+    // Experts of two or three row tiles, where the short tile's extra pass over the weight panel
+    // is a third to a half of the expert's weight traffic, are dealt evenly (Mixtral shape T=1024
+    // -4 %, T=2048 -5 %, Qwen2-MoE shape T=4096 -2 %); with four tiles or more the 224-row bodies
+    // cost what the shared panel saves (gate+up at T=4096 +1.7 %).  Down projection (few, heavy
+    // workgroups): only while the launch is at most two rounds, where equal tiles end together
+    // (T=2048: 538 -> 455 us); with more rounds the quick short tiles fill the gaps better
+    // (T=4096: 864 against 915 us).
+    int row_in = ti * bm, rows = bm;
+    if (even && n >= 2) {
+        const int per = (((n_e + n - 1) / n) + 31) & ~31;   // <= 256
+        row_in = ti * per;
+        rows = per;
+    }
+    rows = (n_e - row_in) < rows ? (n_e - row_in) : rows;
+    if (rows <= 0) return;                              // (n >= 8 only: the rounding can empty the last entry)
     t.e = e;
-    t.row0 = seg0 + r_in;
-    t.rows = (n_e - r_in) < bm ? (n_e - r_in) : bm;
+    t.row0 = seg0 + row_in;
+    t.rows = rows;
     t.n_e = n_e;
     GemmArgs b = a;
     if (t.n_e > a.M) b.rot_mul = a.rot_mul_multi;
@@ -968,6 +994,10 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     {   // development hook: MOE_SIB=0 keeps the plain tile-major order
         const char* e_ = std::getenv("MOE_SIB");
         args.sib = e_ != nullptr ? std::atoi(e_) : 1;
+    }
+    {   // development hook: MOE_EVEN=0 keeps Algorithm 1's row ranges (256, 256, ..., rest), 3 always deals evenly
+        const char* e_ = std::getenv("MOE_EVEN");
+        args.even = e_ != nullptr ? std::atoi(e_) : (GATEUP ? 1 : 2);
     }
     {   // development hook: MOE_CHUNK=0/1 overrides the per-XCD chunking (default: down projection with single-use weights)
         const char* e_ = std::getenv("MOE_CHUNK");

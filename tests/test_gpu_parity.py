@@ -199,8 +199,8 @@ def test_row_tiles_of_an_expert_side_by_side(G, monkeypatch):
     """Experts of three row tiles (two full, one short) on shapes whose feature-tile counts are
     multiples of 8, so that the default kernels re-order the workgroups inside each expert's span
     (row tiles that share a weight panel next to each other on one XCD): every element against the
-    oracle, and bit-equal to the plain tile-major order (same tiles, same arithmetic, different
-    workgroup ids)."""
+    oracle, and bit-equal to the plain tile-major order and to Algorithm 1's row ranges (same
+    per-row arithmetic, different workgroups)."""
     s = mi.MoEShape("three_tiles", 900, 2048, 2048, 3, 2, mi.GATE_SOFTMAX)
     layer = G.Layer(s, seed=11, skew=0.5)
     ref = _oracle_full(layer)
@@ -215,6 +215,14 @@ def test_row_tiles_of_an_expert_side_by_side(G, monkeypatch):
     monkeypatch.delenv("MOE_SIB")
     for name in ("h", "y_perm", "y"):
         assert np.array_equal(out[name], plain[name]), name
+    # the same for the row ranges: by default an expert of two or three row tiles has its rows
+    # dealt evenly over them, MOE_EVEN=0 keeps Algorithm 1's ranges (256, 256, rest)
+    monkeypatch.setenv("MOE_EVEN", "0")
+    _say("three-tile experts, Algorithm 1's row ranges")
+    alg1 = G.run_forward(layer)
+    monkeypatch.delenv("MOE_EVEN")
+    for name in ("h", "y_perm", "y"):
+        assert np.array_equal(out[name], alg1[name]), name
 
 
 def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
