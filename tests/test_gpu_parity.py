@@ -361,6 +361,7 @@ def test_qwen2moe_T4096(G):
 
 
 def test_dsv3_T4096_skewed(G):
-    """Skew 1 at the largest shape: a few experts hold thousands of rows (sixteen 256-row tiles,
-    LDS-DMA body), most a handful (register-staged body), all in one launch."""
+    """Skew 1 at the largest shape: a few experts hold thousands of rows (sixteen 256-row tiles:
+    cached weights, k in step, tiles side by side), most a handful (one short block each:
+    weights streamed once), all in one launch."""
     _sampled_full_size(G, "dsv3", 4096, 3, skew=1.0)
