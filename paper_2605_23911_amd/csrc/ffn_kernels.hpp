@@ -535,7 +535,7 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     };
     // The token tile of step kt+2 (not kt+1) is awaited at the end of step kt, so a tile is
     // visible to every wavefront one whole step before it is used; the first fragments of step
-    // kt+1 can then be read during the last MFMA group of step kt and the MFMAs of the next step
+    // kt+1 can then be read during the last slot of step kt and the MFMAs of the next step
     // start right behind the barrier instead of behind an LDS round trip.
     // The DMA instructions of a step are dealt over its MFMA groups (group g takes q = g, g+NG,
     // ...) behind that group's weight load: the CU's one address unit needs 16 cycles per
@@ -551,8 +551,8 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     bf16x8 xnext[JBE];   // slot-0 fragments of the next step
     // One wavefront per SIMD: while it issues a run of memory instructions nothing feeds the
     // matrix pipe, which holds one MFMA (32 cycles) ahead at most.  So the memory instructions
-    // of a slot (one weight load and at most one token-tile DMA per group, JBE fragment reads
-    // for the next slot) are dealt singly between its NI*JBE MFMAs: fragment jj of the next slot
+    // of a slot (per group one weight load and the group's share of the token-tile DMAs, JBE
+    // fragment reads for the next slot) are dealt singly between its NI*JBE MFMAs: fragment jj of the next slot
     // behind MFMA jj*NI + NI-1, i.e. still NI*JBE - jj*(NI-1) - NI + 1 >= JBE MFMAs before its
     // use.  (Issuing them as one run at the head of each group measured 5 % slower.)
     auto step = [&](int kt, auto u) {
