@@ -140,15 +140,10 @@ def permute_rows(x_bits: np.ndarray, src_of: np.ndarray, k: int) -> np.ndarray:
 
 
 def block_schedule(offsets, M: int):
-    """Algorithm 1: for each expert, ceil(n_e / M) blocks (e, b*M); none if n_e = 0."""
-    blocks = []
-    for e in range(len(offsets) - 1):
-        n_e = int(offsets[e + 1]) - int(offsets[e])
-        b = 0
-        while b * M < n_e:
-            blocks.append((e, b * M))
-            b += 1
-    return blocks
+    """Sec. 3.2's block schedule (Algorithm 1): expert by expert, the row offsets 0, M, 2M, ...
+    below n_e, each paired with the expert id; an expert without rows contributes nothing."""
+    return [(e, r) for e in range(len(offsets) - 1)
+            for r in range(0, int(offsets[e + 1]) - int(offsets[e]), M)]
 
 
 # --------------------------------------------------------------------------- #
