@@ -95,13 +95,16 @@ size_t moe_route_workspace_size(const moe_config* cfg);
 size_t moe_permute_workspace_size(const moe_config* cfg);
 size_t moe_ffn_workspace_size(const moe_config* cfg);
 size_t moe_forward_workspace_size(const moe_config* cfg);
+/* The workspace moe_forward needs: the same value as moe_forward_workspace_size(). */
+size_t moe_workspace_size(const moe_config* cfg);
 /* Fills *out with the layout moe_forward uses; returns MOE_OK or the config error. */
 moe_status moe_forward_workspace_layout(const moe_config* cfg, moe_workspace_layout* out);
 /* Name of the GEMM kernel instance the library launches for this config (stage 0: fused
  * gate+up, 1: down; packed != 0: with moe_pack_weights' layout), e.g. for matching profiler
  * output.  Returns a static string, NULL for an invalid config or stage. */
 const char* moe_ffn_kernel_name(const moe_config* cfg, int32_t stage, int32_t packed);
-/* Upper bound on Alg. 1's block count for tile height M: floor(R/M) + min(E, R). */
+/* Upper bound on Alg. 1's block count for tile height M: floor(R/M) + min(E, R); 0 for an
+ * invalid config or M outside [1, 2^30]. */
 int32_t moe_max_blocks(const moe_config* cfg, int32_t M);
 
 /* Stage 1, router (Eq. 1-2, Sec. 3.4).
@@ -128,11 +131,15 @@ moe_status moe_permute(const moe_config* cfg, const void* x, const int32_t* topk
 
 /* Alg. 1 on the device: blocks [max_blocks,2] int32 = (expert, b*M) in emission order,
  * *num_blocks (device int32) = sum_e ceil(n_e/M).  Entries past *num_blocks are untouched.
- * `blocks` must hold moe_max_blocks(cfg, M) pairs. */
+ * `blocks` must hold moe_max_blocks(cfg, M) pairs.  1 <= M <= 2^30, else MOE_ERR_SHAPE. */
 moe_status moe_block_schedule(const moe_config* cfg, const int32_t* offsets, int32_t M,
                               int32_t* blocks, int32_t* num_blocks, void* stream);
 
-/* Optional one-time weight packing (the weights of an inference layer are static).
+/* One-time weight packing (the weights of an inference layer are static).  THE PACKED COPY IS
+ * THE SERVING LAYOUT: the GEMM kernels are built around it, and a caller that serves traffic
+ * should pack once at load time and pass W_packed from then on.  The row-major tensors of
+ * Sec. 3.2 are accepted by every entry point as the interchange layout (same integers, floats
+ * within the stated tolerance) and run through a slower kernel (about 1.4x at the Mixtral shape).
  * Sec. 3.2 stores each projection as a flattened E*N x K matrix; the GEMM kernels read it
  * through per-lane 16-byte loads whose lanes touch 32 different rows.  moe_pack_weights
  * re-orders the same bf16 values into the order those loads consume them, so that every load

@@ -30,4 +30,5 @@ from .binding import (  # noqa: F401
     permute_workspace_size,
     route_workspace_size,
     tile_m,
+    workspace_size,
 )

@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = (
     "moe_status_string", "moe_tile_m", "moe_route_workspace_size", "moe_permute_workspace_size", "moe_ffn_workspace_size",
-    "moe_forward_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
+    "moe_forward_workspace_size", "moe_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
     "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights", "moe_ffn_kernel_name",
 )
 
@@ -69,7 +69,7 @@ def lib() -> C.CDLL:
     L.moe_max_blocks.restype = C.c_int32
     L.moe_max_blocks.argtypes = [cfgp, C.c_int32]
     for n in ("moe_route_workspace_size", "moe_permute_workspace_size", "moe_ffn_workspace_size", "moe_forward_workspace_size",
-              "moe_packed_weights_size"):
+              "moe_workspace_size", "moe_packed_weights_size"):
         getattr(L, n).restype = C.c_size_t
         getattr(L, n).argtypes = [cfgp]
     L.moe_forward_workspace_layout.restype = C.c_int
@@ -91,6 +91,8 @@ def lib() -> C.CDLL:
     L.moe_forward_staged.restype = C.c_int
     L.moe_forward_staged.argtypes = [cfgp, vp, vp, f32p, vp, vp, vp, vp, vp, vp, C.c_size_t, vp, C.POINTER(C.c_void_p),
                                      C.c_int32]
+    L.moe_test_knob.restype = C.c_int32       # test hook, not part of include/moe.h
+    L.moe_test_knob.argtypes = [C.c_int32, C.c_int32]
     _lib = L
     return L
 
@@ -144,6 +146,19 @@ def ffn_workspace_size(cfg) -> int:
 
 def forward_workspace_size(cfg) -> int:
     return lib().moe_forward_workspace_size(C.byref(cfg))
+
+
+def workspace_size(cfg) -> int:
+    return lib().moe_workspace_size(C.byref(cfg))
+
+
+# Test knobs of the library (csrc/moe_internal.hpp); -1 restores the selection rule.
+KNOB_GATE_UP_VARIANT, KNOB_DOWN_VARIANT, KNOB_SIDE_BY_SIDE, KNOB_EVEN_ROWS, KNOB_XCD_CHUNK, KNOB_ROT = range(6)
+
+
+def test_knob(which: int, value: int) -> int:
+    """Set a test knob; returns the previous value."""
+    return lib().moe_test_knob(which, value)
 
 
 def forward_workspace_layout(cfg) -> WorkspaceLayout:

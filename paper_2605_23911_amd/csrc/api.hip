@@ -1,9 +1,12 @@
 // C ABI of the library (include/moe.h): argument checks on the host, workspace layout, and
 // the stage launchers strung together.  Nothing here allocates, copies or synchronises.
-#include <cstdlib>
 #include <cmath>
 
 #include "moe_internal.hpp"
+
+namespace moe {
+int g_knobs[kNumKnobs] = {-1, -1, -1, -1, -1, -1, -1, -1};
+}
 
 namespace {
 
@@ -53,6 +56,15 @@ moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_
 
 extern "C" {
 
+// Test hook, not declared in include/moe.h: sets one of the knobs of moe_internal.hpp and returns
+// its previous value (-2 for an unknown knob).  value = -1 restores the selection rule.
+int32_t moe_test_knob(int32_t which, int32_t value) {
+    if (which < 0 || which >= kNumKnobs) return -2;
+    const int old = g_knobs[which];
+    g_knobs[which] = value;
+    return old;
+}
+
 const char* moe_status_string(moe_status s) {
     switch (s) {
         case MOE_OK: return "ok";
@@ -87,7 +99,7 @@ const char* moe_ffn_kernel_name(const moe_config* c, int32_t stage, int32_t pack
 }
 
 int32_t moe_max_blocks(const moe_config* c, int32_t M) {
-    if (check_config(c) != MOE_OK || M < 1) return 0;
+    if (check_config(c) != MOE_OK || M < 1 || M > (1 << 30)) return 0;
     const long long R = (long long)c->T * c->k;
     return (int32_t)(R / M + (R < c->E ? R : c->E));
 }
@@ -130,6 +142,8 @@ size_t moe_forward_workspace_size(const moe_config* c) {
     return moe_forward_workspace_layout(c, &l) == MOE_OK ? l.total : 0;
 }
 
+size_t moe_workspace_size(const moe_config* c) { return moe_forward_workspace_size(c); }
+
 moe_status moe_route(const moe_config* c, const void* x, const void* W_r, const float* bias,
                      int32_t* topk_idx, float* topk_w, void* workspace, size_t ws_bytes, void* stream) {
     const moe_status st = check_config(c);
@@ -164,7 +178,7 @@ moe_status moe_block_schedule(const moe_config* c, const int32_t* offsets, int32
                               int32_t* num_blocks, void* stream) {
     const moe_status st = check_config(c);
     if (st != MOE_OK) return st;
-    if (M < 1) return MOE_ERR_SHAPE;
+    if (M < 1 || M > (1 << 30)) return MOE_ERR_SHAPE;   // ceil(n_e / M) is computed as (n_e + M - 1) / M in 32 bits
     if (!offsets || !blocks || !num_blocks) return MOE_ERR_NULL;
     if (c->T == 0) return MOE_OK;
     return hip_status(launch_block_schedule(*c, offsets, M, blocks, num_blocks, (hipStream_t)stream));

@@ -12,13 +12,9 @@ const Variant kDown[] = {
     /*2*/ {64, false, launch_skinny<2, false, 4, 4, false>, "skinny_kernel<2, false, 4, 4, false>"},
     /*3*/ {32, true, launch_skinny<1, false, 4, 4, true>, "skinny_kernel<1, false, 4, 4, true>"},
     /*4*/ {64, true, launch_skinny<2, false, 4, 4, true>, "skinny_kernel<2, false, 4, 4, true>"},
-    /*5*/ {256, true, launch_tile<1, false, 4, 2, true, false>, "tile_kernel<1, false, 4, 2, true, false>"},
-    /*6*/ {256, true, launch_tile<2, false, 2, 1, true, false>, "tile_kernel<2, false, 2, 1, true, false>"},
-    /*7*/ {256, true, launch_tile_dma<1, false, true>, "tile_kernel_dma<1, false, true>"},
-    /*8*/ {256, true, launch_tile_dma<2, false, true>, "tile_kernel_dma<2, false, true>"},
-    /*9*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true>"},
-    /*10*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true>"},
-    /*11*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false>"},
+    /*5*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true>"},
+    /*6*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true>"},
+    /*7*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -35,20 +31,19 @@ int pick(int M, bool packed, const moe_config& c) {
     const bool wide = (long long)(c.d / 256) * (active + R / 256) >= 512;
     if (few_rows && M <= 32) return packed ? 3 : 1;
     if (few_rows && M <= 64) return packed ? 4 : 2;
-    // non-temporal weight loads while experts are single blocks and the token buffers are small
-    const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
     if (!packed) return 0;   // row-major lines are consumed by four loads each: cached loads only
-    // per-block regime selection (tile_kernel_mixed): experts spanning several row tiles take the
-    // LDS-DMA body; with many rows per expert on average the two-weight-block form of it
-    if (once) return wide ? 10 : 9;
-    if ((double)R / c.E > 192.0 || wide) return 11;
-    return 5;
+    // Per-block regime selection (tile_kernel_mixed).  Non-temporal weight loads for single-block
+    // experts while the token buffers are small; with many rows per expert on average, the
+    // two-weight-block form with cached loads throughout.
+    const bool once = (double)R / c.E <= 192.0 && (double)R * c.d * 2.0 <= 128e6;
+    if (once) return wide ? 6 : 5;
+    return 7;
 }
 
 }  // namespace
 
 const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
-    int id = env_variant("MOE_DN_VARIANT", kNumDown, M, packed, kDown);
+    int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);
     return kDown[id].name;
 }
@@ -56,11 +51,29 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
-    GemmArgs a{h, nullptr, 1, c.T * c.k, ldh, c.d, rot_steps(false), rot_steps(true), 0, wd, nullptr, packed_dn, y_perm, offsets, blocks, num_blocks, c.T * c.k, c.d, c.F, 0, M, nullptr};
+    GemmArgs a{};
+    a.X = h;
+    a.src = nullptr;
+    a.src_k = 1;
+    a.x_rows = c.T * c.k;
+    a.ldx = ldh;
+    a.ldo = c.d;
+    a.rot_mul = rot_steps(false);
+    a.rot_mul_multi = rot_steps(true);
+    a.W0 = wd;
+    a.P = packed_dn;
+    a.Out = y_perm;
+    a.offsets = offsets;
+    a.blocks = blocks;
+    a.num_blocks = num_blocks;
+    a.R = c.T * c.k;
+    a.N = c.d;
+    a.K = c.F;
+    a.M = M;
     // token rows are addressed with 32-bit byte offsets from the buffer's base
     if ((unsigned long long)a.x_rows * (unsigned long long)ldh * 2ull >= (1ull << 32)) return hipErrorInvalidValue;
     const bool packed = packed_dn != nullptr;
-    int id = env_variant("MOE_DN_VARIANT", kNumDown, M, packed, kDown);
+    int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);
     if (kDown[id].M < M) return hipErrorInvalidValue;
     return kDown[id].fn(a, moe_max_blocks(&c, M), s);

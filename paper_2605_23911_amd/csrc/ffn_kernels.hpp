@@ -23,8 +23,8 @@
 // Kernels that share that mapping:
 //   tile_kernel        token tile (up to 256 rows) staged in LDS through registers and shared by
 //                      the four wavefronts; body chosen per block from the rows it holds.
-//   tile_kernel_dma    the same tile brought global -> LDS by DMA into a ring of buffers.
-//   tile_kernel_mixed  tile_kernel_dma's body with the regime chosen per block: weights streamed
+//   tile_kernel_mixed  the same tile brought global -> LDS by DMA into a ring of buffers, with
+//                      the regime chosen per block: weights streamed
 //                      once (non-temporal, k rotated) for experts that fit one block, shared
 //                      through L2 (cached, k in step, row tiles side by side) for experts that
 //                      span several (the default for packed weights).
@@ -34,7 +34,6 @@
 //                      where there are too few output rows to fill 256 CUs otherwise).
 #pragma once
 
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -60,7 +59,6 @@ struct GemmArgs {
     const int32_t* num_blocks;  // device scalar
     int R, N, K, n_tiles_n;
     int M;                      // tile height of the block schedule (rows per block <= M)
-    unsigned long long* dbg;   // MOE_STEP_TIMING builds only
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
     int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
     int even;                   // tile_kernel_mixed: rows of a multi-tile expert dealt evenly over its schedule entries
@@ -351,12 +349,6 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
                 make_uint4(xreg[xs_][4 * p + 0], xreg[xs_][4 * p + 1], xreg[xs_][4 * p + 2], xreg[xs_][4 * p + 3]);
         });
     };
-#ifdef MOE_STEP_TIMING
-    unsigned long long tacc[4] = {0, 0, 0, 0};
-#define MOE_TICK(i_) { const unsigned long long now_ = __builtin_readcyclecounter(); tacc[i_] += now_ - tprev; tprev = now_; }
-#else
-#define MOE_TICK(i_)
-#endif
     // One step.  Whatever a wavefront does between MFMAs leaves the matrix pipe idle unless it
     // is issued while an MFMA is still executing (or another wavefront of the SIMD has MFMAs
     // ready).  The weight loads of the prefetched step and the LDS fragment reads of the next
@@ -365,9 +357,6 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     // `u` = kt modulo the unroll factor UNR (a multiple of both STAGES and XD), compile-time.
     auto step = [&](int kt, auto u) {
         const int buf = kt & 1;
-#ifdef MOE_STEP_TIMING
-        unsigned long long tprev = __builtin_readcyclecounter();
-#endif
         constexpr int wst = (u + STAGES - 1) % STAGES;
         const int kw = phys(kt + STAGES - 1);
         load_x(kt + XD, std::integral_constant<int, (u + XD) % XD>{});           // set (kt+XD)%XD == kt%XD
@@ -376,7 +365,6 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
             xf[0][j] = *reinterpret_cast<const bf16x8*>(&xs[buf * BM * kLdsStride + xs_read + j * 32 * kLdsStride]);
         });
         __builtin_amdgcn_sched_barrier(0);
-        MOE_TICK(0)
         static_for<4>([&](auto s) {
             static_for<NI>([&](auto i) {
                 const bf16x8 wf = __builtin_bit_cast(bf16x8, wreg[u % STAGES][i][s]);
@@ -393,12 +381,9 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
                 });
             });
         });
-        MOE_TICK(1)
         store_x(buf ^ 1, std::integral_constant<int, (u + 1) % XD>{});            // token tile of step kt+1
         __builtin_amdgcn_sched_barrier(0);
-        MOE_TICK(2)
         __syncthreads();
-        MOE_TICK(3)
     };
     // NOTE on register sets: in step kt the set kt%XD is free (its tile, step kt, went to LDS at
     // the end of step kt-1), so the loads of step kt+XD reuse it; with XD == 1 the single set is
@@ -411,25 +396,11 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
     __syncthreads();
 
     constexpr int UNR = (STAGES % XD == 0) ? STAGES : STAGES * XD;
-#ifdef MOE_STEP_TIMING
-    const unsigned long long loop_c0 = __builtin_readcyclecounter(), loop_r0 = wall_clock64();
-#endif
     int kt = 0;
     for (; kt + UNR <= KT; kt += UNR) static_for<UNR>([&](auto u) { step(kt + u, u); });
     static_for<UNR>([&](auto u) {
         if (kt + u < KT) step(kt + u, u);
     });
-#ifdef MOE_STEP_TIMING
-    if (a.dbg != nullptr && lane == 0 && wave == 0) {
-        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 0] = __builtin_readcyclecounter() - loop_c0;
-        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 1] = wall_clock64() - loop_r0;
-        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 2] = loop_r0;
-        a.dbg[(1 << 20) + (size_t)blockIdx.x * 4 + 3] = wall_clock64();
-    }
-    if (a.dbg != nullptr && lane == 0 && wave < 4)
-        for (int q = 0; q < 4; ++q) a.dbg[((size_t)blockIdx.x * 4 + wave) * 4 + q] = tacc[q];
-#endif
-#undef MOE_TICK
 
     static_for<IB>([&](auto ib) {
         static_for<JW>([&](auto j) {
@@ -456,11 +427,18 @@ __device__ __forceinline__ void tile_body(const GemmArgs& a, const Tile& t, int 
 // outstanding the N later loads are outstanding too, so the counter is above N; extra operations
 // only lengthen the wait.
 // ---------------------------------------------------------------------------------------------
+// M0 is on the clobber list so that the compiler never orders this statement between its own
+// write of M0 and the instruction that consumes it.  M0 is a reserved (non-allocatable)
+// register, for which clang prints a generic "may not be preserved" warning: overwriting it is
+// exactly what is declared here, so the warning is silenced for this one statement.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma16(const void* gptr, uint32_t lds_addr) {
     const uint32_t base = __builtin_amdgcn_readfirstlane(lds_addr);   // wave-uniform: goes through M0
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit field");
@@ -665,15 +643,6 @@ __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, i
         case 7: return tile_body_dma<8, 7, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
         default: return tile_body_dma<8, 8, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
     }
-}
-
-template <int IB, bool GATEUP, bool PACKED>
-__global__ __launch_bounds__(kThreads) void tile_kernel_dma(const GemmArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
-    Tile t;
-    int tile, nt;
-    if (!map_workgroup(a, tile, nt) || !load_tile(a, tile, 256, t)) return;
-    dma_dispatch<IB, GATEUP, PACKED>(a, t, nt, xs);
 }
 
 // The regime is a property of the EXPERT, not of the launch: under routing skew a few experts
@@ -935,7 +904,7 @@ __global__ __launch_bounds__(kThreads) void skinny_kernel(const GemmArgs a) {
 // feature tiles that share a token tile, walk k together and meet in L2 (measured: a third
 // fewer L2 misses, ~3 % faster at Mixtral T=4096).
 inline int rot_steps(bool dma) {
-    static const int v = std::getenv("MOE_ROT") ? std::atoi(std::getenv("MOE_ROT")) : -1;
+    const int v = knob(kKnobRot);
     return v >= 0 ? v : (dma ? 0 : 2);
 }
 
@@ -952,28 +921,6 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     if (attr != hipSuccess) return attr;
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
-#ifdef MOE_STEP_TIMING
-    args.dbg = std::getenv(GATEUP ? "MOE_DBG_BUF_GU" : "MOE_DBG_BUF_DN")
-                   ? (unsigned long long*)std::strtoull(std::getenv(GATEUP ? "MOE_DBG_BUF_GU" : "MOE_DBG_BUF_DN"), nullptr, 0)
-                   : nullptr;
-#endif
-    const long long grid = (long long)max_blocks * args.n_tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
-    return hipGetLastError();
-}
-
-template <int IB, bool GATEUP, bool PACKED>
-hipError_t launch_tile_dma(const GemmArgs& a, int max_blocks, hipStream_t s) {
-    constexpr int BN = 4 * IB * 32;
-    constexpr int lds = 4 * 8 * 32 * 128;   // XD+1 = 4 buffers of 256 rows x 128 bytes
-    auto kern = tile_kernel_dma<IB, GATEUP, PACKED>;
-    // once per process and kernel: not allowed while a stream is being captured into a graph
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (attr != hipSuccess) return attr;
-    GemmArgs args = a;
-    args.n_tiles_n = (a.N + BN - 1) / BN;
-    args.rot_mul = rot_steps(true);
     const long long grid = (long long)max_blocks * args.n_tiles_n;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
@@ -991,25 +938,16 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     GemmArgs args = a;
     args.n_tiles_n = (a.N + BN - 1) / BN;
     args.rot_mul = rot_steps(false);
-    {   // development hook: MOE_SIB=0 keeps the plain tile-major order
-        const char* e_ = std::getenv("MOE_SIB");
-        args.sib = e_ != nullptr ? std::atoi(e_) : 1;
-    }
-    {   // development hook: MOE_EVEN=0 keeps Algorithm 1's row ranges (256, 256, ..., rest), 3 always deals evenly
-        const char* e_ = std::getenv("MOE_EVEN");
-        args.even = e_ != nullptr ? std::atoi(e_) : (GATEUP ? 1 : 2);
-    }
-    {   // development hook: MOE_CHUNK=0/1 overrides the per-XCD chunking (default: down projection with single-use weights)
-        const char* e_ = std::getenv("MOE_CHUNK");
-        args.chunk = e_ != nullptr ? std::atoi(e_) : (!GATEUP && WNT ? 1 : 0);
-    }
+    // Test knobs (see moe_internal.hpp) can override the three launch-order choices; -1 = the rule.
+    args.sib = knob(kKnobSideBySide) >= 0 ? knob(kKnobSideBySide) : 1;
+    args.even = knob(kKnobEvenRows) >= 0 ? knob(kKnobEvenRows) : (GATEUP ? 1 : 2);
+    args.chunk = knob(kKnobXcdChunk) >= 0 ? knob(kKnobXcdChunk) : (!GATEUP && WNT ? 1 : 0);
     args.rot_mul_multi = rot_steps(true);
     long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking
     args.slots = 0;
     if constexpr (IB == 2 && !GATEUP) {
         static const int cus = [] {
             int dev = 0, n = 0;
-            if (std::getenv("MOE_NO_TAIL_SPLIT") != nullptr) return 0;
             if (hipGetDevice(&dev) != hipSuccess) return 0;
             if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
             return n;
@@ -1039,12 +977,10 @@ struct Variant {
     const char* name;   // kernel template instance, as rocprofv3 prints it (minus namespaces)
 };
 
-// A tuning run may force a variant by table index through an environment variable; the index
-// is ignored unless that variant matches the tile height and weight layout in use.
-inline int env_variant(const char* name, int count, int M, bool packed, const Variant* table) {
-    const char* v = std::getenv(name);
-    if (v == nullptr) return -1;
-    const int id = std::atoi(v);
+// A test may force a variant by table index through a knob; the index is ignored unless that
+// variant matches the tile height and weight layout in use.
+inline int forced_variant(int which, int count, int M, bool packed, const Variant* table) {
+    const int id = knob(which);
     return (id >= 0 && id < count && table[id].M >= M && table[id].packed == packed) ? id : -1;
 }
 

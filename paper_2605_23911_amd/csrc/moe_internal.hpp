@@ -35,6 +35,23 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// ---- test knobs -------------------------------------------------------------------------
+// Process-wide integer switches that GPU tests set through moe_test_knob() (exported from the
+// library, deliberately absent from include/moe.h: not part of the product interface) to force
+// code paths that the selection rules would not take at test sizes.  -1 = "follow the rule".
+// Nothing reads the process environment.
+enum {
+    kKnobGateUpVariant = 0,   // index into the gate+up variant table
+    kKnobDownVariant = 1,     // index into the down-projection variant table
+    kKnobSideBySide = 2,      // 0: plain tile-major order inside multi-tile experts
+    kKnobEvenRows = 3,        // 0: Algorithm 1's row ranges everywhere, 3: every multi-tile expert dealt evenly
+    kKnobXcdChunk = 4,        // 0/1: per-XCD contiguous chunks off/on for both projections
+    kKnobRot = 5,             // k-loop rotation between the workgroups of an XCD, in steps
+    kNumKnobs = 8
+};
+extern int g_knobs[kNumKnobs];
+inline int knob(int i) { return g_knobs[i]; }
+
 // ---- launchers (each enqueues on `s` and returns hipGetLastError()) ----------------------
 // workspace: route_workspace_bytes(c) bytes of fp64 partial logit tiles
 size_t route_workspace_bytes(const moe_config& c);
