@@ -20,18 +20,14 @@ def bits_to_f64(u16: np.ndarray) -> np.ndarray:
     return (u16.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
-class Layer:
-    """One seeded layer: CPU bit patterns for the oracle and device tensors for the library."""
+class Bank:
+    """The expert weights of one layer shape (they depend on d, F, E and the seed, not on T or
+    the routing skew): device tensors, the one-time packed copy, and optionally the CPU bit
+    patterns.  Several Layer objects (different T, different skew) can share one bank."""
 
-    def __init__(self, shape: mi.MoEShape, seed: int = 0, skew: float = 0.0, keep_cpu_weights: bool = True):
+    def __init__(self, shape: mi.MoEShape, seed: int = 0, keep_cpu_weights: bool = True):
         self.shape = shape
         self.seed = seed
-        self.x_cpu = mi.make_x(shape, seed)
-        self.wr_cpu = mi.make_router(shape, seed)
-        self.bias_cpu = mi.skew_bias(shape, skew, seed)
-        self.x = self.x_cpu.to(DEV)
-        self.wr = self.wr_cpu.to(DEV)
-        self.bias = None if self.bias_cpu is None else self.bias_cpu.to(DEV)
         s = shape
         self.wg = torch.empty((s.E, s.F, s.d), dtype=torch.bfloat16, device=DEV)
         self.wu = torch.empty((s.E, s.F, s.d), dtype=torch.bfloat16, device=DEV)
@@ -45,18 +41,44 @@ class Layer:
         else:
             mi.make_all_experts(s, seed, out=(self.wg, self.wu, self.wd))
         # one-time packed copy of the expert weights (what a serving stack does at load time)
-        self.packed = torch.empty(moe.packed_weights_size(self.cfg()), dtype=torch.uint8, device=DEV)
-        moe.moe_pack_weights(self.cfg(), self.wg, self.wu, self.wd, self.packed)
+        cfg = moe.MoEConfig.of(1, s.d, s.F, s.E, s.k, s.gating)
+        self.packed = torch.empty(moe.packed_weights_size(cfg), dtype=torch.uint8, device=DEV)
+        moe.moe_pack_weights(cfg, self.wg, self.wu, self.wd, self.packed)
         torch.cuda.synchronize()
+
+    def expert_bits(self, e: int):
+        """Oracle-side weight provider: regenerates the expert from its seed when not cached."""
+        w = self._cpu_w[e] if self._cpu_w is not None else mi.make_expert(self.shape, e, self.seed)
+        return tuple(mi.bits(t) for t in w)
+
+
+class Layer:
+    """One seeded layer: CPU bit patterns for the oracle and device tensors for the library."""
+
+    def __init__(self, shape: mi.MoEShape, seed: int = 0, skew: float = 0.0, keep_cpu_weights: bool = True,
+                 bank: Bank | None = None):
+        self.shape = shape
+        self.seed = seed
+        self.x_cpu = mi.make_x(shape, seed)
+        self.wr_cpu = mi.make_router(shape, seed)
+        self.bias_cpu = mi.skew_bias(shape, skew, seed)
+        self.x = self.x_cpu.to(DEV)
+        self.wr = self.wr_cpu.to(DEV)
+        self.bias = None if self.bias_cpu is None else self.bias_cpu.to(DEV)
+        if bank is None:
+            bank = Bank(shape, seed, keep_cpu_weights)
+        else:
+            b = bank.shape
+            assert (b.d, b.F, b.E, b.k, b.gating, bank.seed) == (shape.d, shape.F, shape.E, shape.k, shape.gating, seed)
+        self.bank = bank
+        self.wg, self.wu, self.wd, self.packed = bank.wg, bank.wu, bank.wd, bank.packed
 
     def cfg(self, tile_m: int = 0, T: int | None = None):
         s = self.shape
         return moe.MoEConfig.of(s.T if T is None else T, s.d, s.F, s.E, s.k, s.gating, tile_m)
 
     def expert_bits(self, e: int):
-        """Oracle-side weight provider: regenerates the expert from its seed when not cached."""
-        w = self._cpu_w[e] if self._cpu_w is not None else mi.make_expert(self.shape, e, self.seed)
-        return tuple(mi.bits(t) for t in w)
+        return self.bank.expert_bits(e)
 
     @property
     def x_bits(self):

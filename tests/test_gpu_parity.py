@@ -195,56 +195,136 @@ def test_forward_equals_the_stage_entry_points(G, shape):
     assert np.array_equal(y_bits, out["y"])
 
 
-def test_row_tiles_of_an_expert_side_by_side(G, monkeypatch):
+@pytest.fixture
+def knobs():
+    """Sets test knobs of the library for one test and restores the selection rules afterwards."""
+    import paper_2605_23911_amd.binding as B
+    touched = []
+
+    def set_knob(which, value):
+        touched.append(which)
+        B.test_knob(which, value)
+
+    yield set_knob
+    for which in touched:
+        B.test_knob(which, -1)
+
+
+def _all_rows_against_oracle(G, layer, ref, out):
+    """Every element of h, y_perm and y against the full oracle; no row left unwritten."""
+    _check_routing(out, ref, layer)
+    _check_floats(out, ref, layer, G)
+    assert (out["h"] != 0).any(axis=1).all(), "a row of h was never written"
+    assert (out["y_perm"] != 0).any(axis=1).all(), "a row of y_perm was never written"
+
+
+def test_row_tiles_of_an_expert_side_by_side(G, knobs):
     """Experts of three row tiles (two full, one short) on shapes whose feature-tile counts are
     multiples of 8, so that the default kernels re-order the workgroups inside each expert's span
     (row tiles that share a weight panel next to each other on one XCD): every element against the
     oracle, and bit-equal to the plain tile-major order and to Algorithm 1's row ranges (same
     per-row arithmetic, different workgroups)."""
+    import paper_2605_23911_amd.binding as B
     s = mi.MoEShape("three_tiles", 900, 2048, 2048, 3, 2, mi.GATE_SOFTMAX)
     layer = G.Layer(s, seed=11, skew=0.5)
     ref = _oracle_full(layer)
     assert (ref["counts"] > 512).any() and (ref["counts"] % 256 != 0).all()
     _say("three-tile experts, side-by-side launch order")
     out = G.run_forward(layer)
-    _check_routing(out, ref, layer)
-    _check_floats(out, ref, layer, G)
-    monkeypatch.setenv("MOE_SIB", "0")
+    _all_rows_against_oracle(G, layer, ref, out)
+    knobs(B.KNOB_SIDE_BY_SIDE, 0)
     _say("three-tile experts, tile-major launch order")
     plain = G.run_forward(layer)
-    monkeypatch.delenv("MOE_SIB")
+    knobs(B.KNOB_SIDE_BY_SIDE, -1)
     for name in ("h", "y_perm", "y"):
         assert np.array_equal(out[name], plain[name]), name
     # the same for the row ranges: by default an expert of two or three row tiles has its rows
-    # dealt evenly over them, MOE_EVEN=0 keeps Algorithm 1's ranges (256, 256, rest)
-    monkeypatch.setenv("MOE_EVEN", "0")
+    # dealt evenly over them; knob 0 keeps Algorithm 1's ranges (256, 256, rest)
+    knobs(B.KNOB_EVEN_ROWS, 0)
     _say("three-tile experts, Algorithm 1's row ranges")
     alg1 = G.run_forward(layer)
-    monkeypatch.delenv("MOE_EVEN")
     for name in ("h", "y_perm", "y"):
         assert np.array_equal(out[name], alg1[name]), name
 
 
-def test_lds_dma_variants_and_graph_replay(G, monkeypatch):
-    """The GEMM kernels that stage EVERY token tile with LDS-DMA loads (selected by environment
-    variable; the default kernel uses that body only for experts spanning several row tiles)
-    against the oracle, and a HIP-graph capture of moe_forward on the default path (one expert
-    with two row tiles, the rest single blocks) whose replays must equal the eager result bit for
-    bit (the library enqueues kernels only)."""
+# Shapes for the launch orders of multi-tile experts, all rows checked.  d = 2048 and F = 1024
+# give feature-tile counts that are multiples of 8 for both projections (F/128 = 8; d/128 = 16,
+# d/256 = 8), which is what switches the side-by-side order on.
+#   five_tiles : 2 experts x 1100 rows = 4 full tiles + 76 rows.  gate+up: side by side with the
+#                short tile moved to the end of the span (n = 5, n - 1 tiles in step).  down: 80
+#                two-block workgroups are at most half a round, so each is split into two
+#                128-feature halves.
+#   nine_tiles : 2 experts x 2100 rows = 8 full tiles + 52 rows.  Both projections side by side
+#                with the short tile at the end; the down projection in its two-weight-block form.
+#   skewed16   : 16 experts under skew 2: one of 4 full tiles + a short one, one of three tiles,
+#                one of two, the rest single blocks or empty, in one launch.  down: single-use
+#                weights, one contiguous eighth of the work per XCD.
+_TILE_SHAPES = {
+    "five_tiles": (mi.MoEShape("five_tiles", 1100, 2048, 1024, 2, 2, mi.GATE_SOFTMAX), 11, 0.0),
+    "nine_tiles": (mi.MoEShape("nine_tiles", 2100, 2048, 1024, 2, 2, mi.GATE_SOFTMAX_RENORM), 12, 0.0),
+    "skewed16": (mi.MoEShape("skewed16", 1090, 2048, 1024, 16, 2, mi.GATE_SOFTMAX), 11, 2.0),
+}
+
+
+@pytest.mark.parametrize("name", sorted(_TILE_SHAPES))
+def test_multi_tile_experts_all_rows(G, knobs, name):
+    """Experts of four and more row tiles with a short last one, every element of h, y_perm and
+    y against the oracle, in each launch order the kernels have: side by side with the short
+    tile at the end of the span, a last round split in halves, per-XCD chunks; then bit-equal
+    results with each re-ordering switched off and with the rows dealt evenly."""
     import paper_2605_23911_amd as moe
+    import paper_2605_23911_amd.binding as B
+    s, seed, skew = _TILE_SHAPES[name]
+    layer = G.Layer(s, seed=seed, skew=skew)
+    ref = _oracle_full(layer)
+    hot = int(ref["counts"].max())
+    assert hot > 4 * 256 and 0 < hot % 256 <= 96, "the fullest expert must end in a short tile"
+    cfg = layer.cfg()
+    if name == "five_tiles":
+        assert moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<2, false, true, false")
+    if name == "skewed16":
+        assert moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<1, false, true, true")
+        assert sorted(ref["counts"])[-2] > 512 and sorted(ref["counts"])[-3] > 256
+    _say(f"{name}: default launch order, all rows")
+    out = G.run_forward(layer)
+    _all_rows_against_oracle(G, layer, ref, out)
+    for which, value, label in [(B.KNOB_SIDE_BY_SIDE, 0, "tile-major order"), (B.KNOB_EVEN_ROWS, 0, "Algorithm 1's row ranges"),
+                                (B.KNOB_EVEN_ROWS, 3, "rows dealt evenly everywhere")]:
+        knobs(which, value)
+        _say(f"{name}: {label}")
+        other = G.run_forward(layer)
+        knobs(which, -1)
+        for key in ("h", "y_perm", "y"):
+            assert np.array_equal(out[key], other[key]), (label, key)
+    # The per-XCD chunking changes which workgroup id computes a block, and single-block experts
+    # start their k loop at a step that depends on the id: another order of the same sum, so
+    # these two are compared with the oracle, not bit for bit.
+    for value, label in [(0, "no per-XCD chunks"), (1, "per-XCD chunks on both projections")]:
+        knobs(B.KNOB_XCD_CHUNK, value)
+        _say(f"{name}: {label}")
+        other = G.run_forward(layer)
+        knobs(B.KNOB_XCD_CHUNK, -1)
+        _all_rows_against_oracle(G, layer, ref, other)
+
+
+def test_down_projection_variants_and_graph_replay(G, knobs):
+    """Every packed down-projection kernel forced onto the ragged shape (the selection rules
+    would pick only one of them at this size) against the oracle, and a HIP-graph capture of
+    moe_forward on the default path (one expert with two row tiles, the rest single blocks)
+    whose replays must equal the eager result bit for bit (the library enqueues kernels only)."""
+    import paper_2605_23911_amd as moe
+    import paper_2605_23911_amd.binding as B
     s = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
     layer = G.Layer(s, seed=3, skew=2.0)
     ref = _oracle_full(layer)
-    monkeypatch.setenv("MOE_GU_VARIANT", "3")
-    monkeypatch.setenv("MOE_DN_VARIANT", "7")
     cfg = layer.cfg()
-    assert "dma" in moe.ffn_kernel_name(cfg, 0, True) and "dma" in moe.ffn_kernel_name(cfg, 1, True)
-    _say("LDS-DMA variants on the ragged shape")
-    out = G.run_forward(layer)
-    _check_routing(out, ref, layer)
-    _check_floats(out, ref, layer, G)
-    monkeypatch.delenv("MOE_GU_VARIANT")
-    monkeypatch.delenv("MOE_DN_VARIANT")
+    for variant, frag in [(5, "mixed<1, false, true, true"), (6, "mixed<2, false, true, true"), (7, "mixed<2, false, true, false")]:
+        knobs(B.KNOB_DOWN_VARIANT, variant)
+        assert frag in moe.ffn_kernel_name(cfg, 1, True)
+        _say(f"down-projection variant {variant} on the ragged shape")
+        out = G.run_forward(layer)
+        _all_rows_against_oracle(G, layer, ref, out)
+    knobs(B.KNOB_DOWN_VARIANT, -1)
     _say("graph capture + replays of the default path")
     lay = moe.forward_workspace_layout(cfg)
     ws = torch.zeros(lay.total, dtype=torch.uint8, device=G.DEV)
@@ -304,64 +384,5 @@ def test_permutation_and_schedule_bit_exact(G, T, E, k, alpha):
         assert [tuple(b) for b in blocks.tolist()] == want
 
 
-# ----------------------------------------------------------------------------- full-size configs, sampled rows
-def _sampled_full_size(G, preset, T, n_tok, skew=0.0, packed=True):
-    s = mi.PRESETS[preset].with_T(T)
-    _say(f"{preset} T={T} skew={skew}: generating weights")
-    layer = G.Layer(s, seed=0, skew=skew, keep_cpu_weights=False)
-    _say(f"{preset} T={T}: moe_forward packed={packed}")
-    out = G.run_forward(layer, packed=packed)
-    _say(f"{preset} T={T}: oracle routing on all tokens, FFN on {n_tok} sampled tokens")
-    idx_ref, _, _ = orc.route(layer.x_bits, layer.wr_bits, layer.bias_np, s.k, s.gating)
-    counts = np.bincount(idx_ref.reshape(-1), minlength=s.E)
-    hot = int(np.argmax(counts))
-    cold = int(np.argmin(np.where(counts > 0, counts, counts.max() + 1)))
-    rng = np.random.default_rng(1)
-    tokens = set(rng.choice(T, size=min(n_tok, T), replace=False).tolist())
-    tokens.add(int(np.nonzero((idx_ref == hot).any(axis=1))[0][0]))      # a row of the fullest expert
-    tokens.add(int(np.nonzero((idx_ref == cold).any(axis=1))[0][-1]))    # and of the emptiest non-empty one
-    ref = orc.moe_forward(layer.x_bits, layer.wr_bits, layer.bias_np, layer.expert_bits, s.k, s.gating,
-                          tokens=sorted(tokens), keep_h=True)
-    _check_routing(out, ref, layer)
-    _check_floats(out, ref, layer, G)
-    del layer
-    torch.cuda.empty_cache()
-
-
-def test_mixtral_T512_bench_configuration(G):
-    _sampled_full_size(G, "mixtral", 512, 6)
-
-
-def test_mixtral_T64_weight_bound_regime(G):
-    _sampled_full_size(G, "mixtral", 64, 4)
-
-
-def test_mixtral_T512_row_major_weights(G):
-    _sampled_full_size(G, "mixtral", 512, 4, packed=False)
-
-
-def test_mixtral_T4096_mfma_bound_regime(G):
-    _sampled_full_size(G, "mixtral", 4096, 6)
-
-
-def test_qwen2moe_T512_skewed(G):
-    _sampled_full_size(G, "qwen2moe", 512, 6, skew=1.5)
-
-
-def test_dsv3_T512(G):
-    _sampled_full_size(G, "dsv3", 512, 3)
-
-
-def test_mixtral_T1_decode(G):
-    _sampled_full_size(G, "mixtral", 1, 1)
-
-
-def test_qwen2moe_T4096(G):
-    _sampled_full_size(G, "qwen2moe", 4096, 4)
-
-
-def test_dsv3_T4096_skewed(G):
-    """Skew 1 at the largest shape: a few experts hold thousands of rows (sixteen 256-row tiles:
-    cached weights, k in step, tiles side by side), most a handful (one short block each:
-    weights streamed once), all in one launch."""
-    _sampled_full_size(G, "dsv3", 4096, 3, skew=1.0)
+# The full-size configurations of the benchmark contract (every T of every shape, the skew grid,
+# the second workload sweep) are in test_gpu_contract_cells.py.
