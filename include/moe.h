@@ -129,6 +129,23 @@ moe_status moe_permute(const moe_config* cfg, const void* x, const int32_t* topk
                        int32_t* counts, int32_t* offsets, int32_t* row_of, int32_t* src_of,
                        void* x_perm, void* workspace, size_t ws_bytes, void* stream);
 
+/* moe_permute for callers that cannot allocate device memory and have no workspace to hand in
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same results as moe_permute, with the chunk histograms (the only scratch the
+ * stage needs: ceil(R/1024) * E int32) in a file-scope device array of the library instead of a
+ * workspace argument.  The array holds MOE_PERMUTE_STATIC_MAX_INTS int32 (256 KiB) on every GPU
+ * the library is used on, for the life of the process.  A configuration with
+ * ceil(T*k/1024) * E above that returns MOE_ERR_UNSUPPORTED.  The call allocates nothing and frees
+ * nothing.  Nothing in the array has to start at zero (every entry that is read has been written
+ * earlier in the same call), so it is never cleared; its contents after a call are unspecified.
+ * All calls on one GPU share the one array: two calls whose kernels overlap on the same GPU
+ * (different streams, or different host threads on different streams) race and give wrong
+ * results; calls on one stream are ordered and safe. */
+#define MOE_PERMUTE_STATIC_MAX_INTS 65536
+moe_status moe_permute_static(const moe_config* cfg, const void* x, const int32_t* topk_idx,
+                              int32_t* counts, int32_t* offsets, int32_t* row_of, int32_t* src_of,
+                              void* x_perm, void* stream);
+
 /* Alg. 1 on the device: blocks [max_blocks,2] int32 = (expert, b*M) in emission order,
  * *num_blocks (device int32) = sum_e ceil(n_e/M).  Entries past *num_blocks are untouched.
  * `blocks` must hold moe_max_blocks(cfg, M) pairs.  1 <= M <= 2^30, else MOE_ERR_SHAPE. */

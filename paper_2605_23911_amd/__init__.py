@@ -26,6 +26,7 @@ from .binding import (  # noqa: F401
     moe_pack_weights,
     packed_weights_size,
     moe_permute,
+    moe_permute_static,
     moe_route,
     permute_workspace_size,
     route_workspace_size,

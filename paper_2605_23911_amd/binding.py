@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = (
     "moe_status_string", "moe_tile_m", "moe_route_workspace_size", "moe_permute_workspace_size", "moe_ffn_workspace_size",
     "moe_forward_workspace_size", "moe_workspace_size", "moe_forward_workspace_layout", "moe_max_blocks", "moe_route",
-    "moe_permute", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights", "moe_ffn_kernel_name",
+    "moe_permute", "moe_permute_static", "moe_block_schedule", "moe_grouped_ffn", "moe_combine", "moe_forward", "moe_forward_staged", "moe_packed_weights_size", "moe_pack_weights", "moe_ffn_kernel_name",
 )
 
 
@@ -78,6 +78,8 @@ def lib() -> C.CDLL:
     L.moe_route.argtypes = [cfgp, vp, vp, f32p, i32p, f32p, vp, C.c_size_t, vp]
     L.moe_permute.restype = C.c_int
     L.moe_permute.argtypes = [cfgp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, C.c_size_t, vp]
+    L.moe_permute_static.restype = C.c_int
+    L.moe_permute_static.argtypes = [cfgp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp]
     L.moe_block_schedule.restype = C.c_int
     L.moe_block_schedule.argtypes = [cfgp, i32p, C.c_int32, i32p, i32p, vp]
     L.moe_grouped_ffn.restype = C.c_int
@@ -176,6 +178,11 @@ def moe_permute(cfg, x, topk_idx, counts, offsets, row_of, src_of, x_perm, works
     _check(lib().moe_permute(C.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(row_of),
                              _ptr(src_of), _ptr(x_perm), _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "moe_permute")
+
+
+def moe_permute_static(cfg, x, topk_idx, counts, offsets, row_of, src_of, x_perm, stream=None):
+    _check(lib().moe_permute_static(C.byref(cfg), _ptr(x), _ptr(topk_idx), _ptr(counts), _ptr(offsets), _ptr(row_of),
+                                    _ptr(src_of), _ptr(x_perm), _stream(stream)), "moe_permute_static")
 
 
 def moe_block_schedule(cfg, offsets, M, blocks, num_blocks, stream=None):

@@ -174,6 +174,26 @@ moe_status moe_permute(const moe_config* c, const void* x, const int32_t* topk_i
     return hip_status(e);
 }
 
+moe_status moe_permute_static(const moe_config* c, const void* x, const int32_t* topk_idx, int32_t* counts,
+                              int32_t* offsets, int32_t* row_of, int32_t* src_of, void* x_perm, void* stream) {
+    const moe_status st = check_config(c);
+    if (st != MOE_OK) return st;
+    if (!topk_idx || !counts || !offsets || !row_of || !src_of) return MOE_ERR_NULL;
+    if ((x == nullptr) != (x_perm == nullptr)) return MOE_ERR_NULL;
+    if (misaligned(x) || misaligned(x_perm)) return MOE_ERR_ALIGN;
+    // the chunk histograms [chunks, E] must fit the file-scope array
+    if ((size_t)permute_chunks(*c) * (size_t)c->E > (size_t)MOE_PERMUTE_STATIC_MAX_INTS) return MOE_ERR_UNSUPPORTED;
+    if (c->T == 0) return MOE_OK;
+    int32_t* hist = nullptr;
+    hipError_t e = permute_static_scratch(&hist);
+    hipStream_t s = (hipStream_t)stream;
+    if (e == hipSuccess)
+        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, 0, nullptr, nullptr, s);
+    if (e == hipSuccess && x != nullptr)
+        e = launch_gather_rows(*c, (const uint16_t*)x, src_of, (uint16_t*)x_perm, c->d, s);
+    return hip_status(e);
+}
+
 moe_status moe_block_schedule(const moe_config* c, const int32_t* offsets, int32_t M, int32_t* blocks,
                               int32_t* num_blocks, void* stream) {
     const moe_status st = check_config(c);

@@ -63,6 +63,9 @@ hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* 
 hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
                                 int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s);
+// Device address of the current GPU's file-scope scratch array (MOE_PERMUTE_STATIC_MAX_INTS
+// int32) that moe_permute_static hands to launch_permute_index in place of a caller workspace.
+hipError_t permute_static_scratch(int32_t** ptr);
 hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int32_t* src_of,
                               uint16_t* x_perm, int32_t ld_perm, hipStream_t s);
 hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M,

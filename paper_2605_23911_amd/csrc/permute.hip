@@ -3,11 +3,20 @@
 // (block schedule).  The paper sorts with a library call and builds the schedule on the host
 // behind a device->host sync (its limitation 2); here a three-kernel counting sort keeps
 // everything on the stream: per-chunk histograms, one scan, per-chunk stable ranks.
+#include <mutex>
+
 #include "moe_internal.hpp"
 
 namespace moe {
 
 namespace {
+
+// Chunk histograms for moe_permute_static, the entry point for callers that cannot allocate:
+// one array per GPU, held from the moment the library's code object is loaded on that GPU until
+// the process ends.  In host code the name below is only a handle for hipGetSymbolAddress: the
+// kernels are given the device address that call returns, never the name.
+constexpr size_t kStaticScratchInts = MOE_PERMUTE_STATIC_MAX_INTS;
+static __device__ __align__(256) int32_t scratch[kStaticScratchInts];
 
 constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
@@ -295,6 +304,28 @@ __global__ __launch_bounds__(kThreads) void gather_kernel(const uint16_t* __rest
 }
 
 }  // namespace
+
+// Device address of this GPU's copy of `scratch`, looked up once per device (with that device
+// current) and kept.  No allocation happens here or later.
+hipError_t permute_static_scratch(int32_t** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static int32_t* per_device[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(lock);
+    if (per_device[dev] == nullptr) {
+        int32_t* p = nullptr;
+        e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    return hipSuccess;
+}
 
 hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
