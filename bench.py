@@ -44,6 +44,8 @@ def parse_args():
     ap.add_argument("--cpu-sample", type=int, default=0, help="tokens the oracle's FFN is timed on (0 = auto)")
     ap.add_argument("--row-major", action="store_true",
                     help="feed the GEMMs the row-major [E,N,K] weights instead of the one-time packed copy")
+    ap.add_argument("--fuse-combine", action="store_true",
+                    help="set MOE_FLAG_FUSE_COMBINE: the weighted combine runs inside the down projection")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -97,7 +99,8 @@ def main():
     wu = torch.empty((s.E, s.F, s.d), dtype=torch.bfloat16, device=dev)
     wd = torch.empty((s.E, s.d, s.F), dtype=torch.bfloat16, device=dev)
     mi.make_all_experts(s, args.seed, out=(wg, wu, wd))
-    cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating, args.tile_m)
+    cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating, args.tile_m,
+                           moe.FLAG_FUSE_COMBINE if args.fuse_combine else 0)
     packed = None
     if not args.row_major:      # model-load-time step, outside every timed region: same values, re-ordered
         packed = torch.empty(moe.packed_weights_size(cfg), dtype=torch.uint8, device=dev)

@@ -59,11 +59,22 @@ typedef enum {
     MOE_GATE_SIGMOID_NORM = 2    /* w_i = sigmoid(z_{e_i}) / sum_j sigmoid(z_{e_j})  (Sec. 3.4) */
 } moe_gating;
 
+/* moe_config.flags */
+/* moe_forward folds the weighted combine (Eq. 3) into the down projection instead of launching
+ * it as a fifth kernel (the paper's limitation 1): the workgroup that writes the last of a token's
+ * k expert rows sums them, in slot order, from the bf16 rows in memory, so y is bit-identical to
+ * moe_combine's whichever workgroup arrives last.  One launch fewer per layer; the GEMM
+ * workgroups pay for it with latency-bound reads at their end, which costs more than the launch
+ * it saves once T*k exceeds a few hundred rows (measured), so it is off unless asked for.
+ * Needs packed weights and more than a handful of rows (the kernels that serve row-major weights
+ * and the K-split kernel have no such epilogue): otherwise the flag is ignored. */
+#define MOE_FLAG_FUSE_COMBINE 1
+
 typedef struct {
     int32_t T, d, F, E, k;
     int32_t gating;       /* moe_gating */
     int32_t tile_m;       /* rows per block-schedule tile (Alg. 1's M); 0 = chosen from T*k/E */
-    int32_t reserved;     /* must be 0 */
+    int32_t flags;        /* bit set of MOE_FLAG_*; unknown bits are refused (MOE_ERR_SHAPE) */
 } moe_config;
 
 /* Byte offsets of moe_forward's intermediates inside its workspace (all 256-byte aligned). */

@@ -5,6 +5,7 @@ the path runs in the HIP library.  There is no CPU fallback: calling an entry po
 the built library raises.
 """
 from .binding import (  # noqa: F401
+    FLAG_FUSE_COMBINE,
     GATE_SIGMOID_NORM,
     GATE_SOFTMAX,
     GATE_SOFTMAX_RENORM,

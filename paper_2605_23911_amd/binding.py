@@ -13,6 +13,7 @@ import torch  # imported before the library so that both share one HIP runtime
 GATE_SOFTMAX = 0
 GATE_SOFTMAX_RENORM = 1
 GATE_SIGMOID_NORM = 2
+FLAG_FUSE_COMBINE = 1
 
 _LIB_NAME = "libmoe_mi355x.so"
 _lib = None
@@ -33,11 +34,11 @@ class MoEError(RuntimeError):
 
 class MoEConfig(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("F", C.c_int32), ("E", C.c_int32), ("k", C.c_int32),
-                ("gating", C.c_int32), ("tile_m", C.c_int32), ("reserved", C.c_int32)]
+                ("gating", C.c_int32), ("tile_m", C.c_int32), ("flags", C.c_int32)]
 
     @classmethod
-    def of(cls, T, d, F, E, k, gating=GATE_SOFTMAX, tile_m=0):
-        return cls(T, d, F, E, k, gating, tile_m, 0)
+    def of(cls, T, d, F, E, k, gating=GATE_SOFTMAX, tile_m=0, flags=0):
+        return cls(T, d, F, E, k, gating, tile_m, flags)
 
 
 class WorkspaceLayout(C.Structure):
@@ -155,7 +156,8 @@ def workspace_size(cfg) -> int:
 
 
 # Test knobs of the library (csrc/moe_internal.hpp); -1 restores the selection rule.
-KNOB_GATE_UP_VARIANT, KNOB_DOWN_VARIANT, KNOB_SIDE_BY_SIDE, KNOB_EVEN_ROWS, KNOB_XCD_CHUNK, KNOB_ROT = range(6)
+(KNOB_GATE_UP_VARIANT, KNOB_DOWN_VARIANT, KNOB_SIDE_BY_SIDE, KNOB_EVEN_ROWS, KNOB_XCD_CHUNK, KNOB_ROT, KNOB_SHORT_NT,
+ KNOB_FUSE_COMBINE) = range(8)
 
 
 def test_knob(which: int, value: int) -> int:

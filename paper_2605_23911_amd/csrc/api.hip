@@ -28,7 +28,7 @@ moe_status check_config(const moe_config* c) {
     if (c == nullptr) return MOE_ERR_NULL;
     if (c->T < 0 || c->d < 1 || c->F < 1 || c->E < 1 || c->k < 1 || c->k > c->E) return MOE_ERR_SHAPE;
     if (c->gating < MOE_GATE_SOFTMAX || c->gating > MOE_GATE_SIGMOID_NORM) return MOE_ERR_SHAPE;
-    if (c->reserved != 0) return MOE_ERR_SHAPE;
+    if ((c->flags & ~MOE_FLAG_FUSE_COMBINE) != 0) return MOE_ERR_SHAPE;
     if (c->tile_m != 0 && !valid_tile_m(c->tile_m)) return MOE_ERR_SHAPE;
     if (c->E > kMaxExperts) return MOE_ERR_UNSUPPORTED;
     if (c->d % 64 != 0 || c->F % 64 != 0) return MOE_ERR_UNSUPPORTED;
@@ -45,12 +45,18 @@ size_t schedule_bytes(const moe_config* c, int M) {
     return align_up((size_t)moe_max_blocks(c, M) * 2 * sizeof(int32_t)) + kAlign;   // + num_blocks
 }
 
+size_t arrive_bytes(const moe_config* c) {
+    return align_up((size_t)(c->T > 0 ? c->T : 1) * combine_groups(*c) * sizeof(int32_t));
+}
+
 size_t hist_bytes(const moe_config* c) {
     size_t n = (size_t)permute_chunks(*c) * c->E * sizeof(int32_t);
     return align_up(n ? n : 1);
 }
 
 moe_status hip_status(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_ERR_HIP; }
+
+
 
 }  // namespace
 
@@ -132,7 +138,7 @@ moe_status moe_forward_workspace_layout(const moe_config* c, moe_workspace_layou
     out->x_perm = take(0);   // moe_forward gathers rows inside the gate+up loads: no permuted copy of x
     out->h = take(R * c->F * sizeof(uint16_t));
     out->y_perm = take(R * c->d * sizeof(uint16_t));
-    out->scratch = take(moe_route_workspace_size(c) + hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)));
+    out->scratch = take(moe_route_workspace_size(c) + hist_bytes(c) + schedule_bytes(c, moe_tile_m(c)) + arrive_bytes(c));
     out->total = off;
     return MOE_OK;
 }
@@ -153,7 +159,7 @@ moe_status moe_route(const moe_config* c, const void* x, const void* W_r, const 
     if (ws_bytes < moe_route_workspace_size(c)) return MOE_ERR_WORKSPACE;
     if (c->T == 0) return MOE_OK;
     return hip_status(launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, workspace,
-                                   (hipStream_t)stream));
+                                   nullptr, 0, (hipStream_t)stream));
 }
 
 moe_status moe_permute(const moe_config* c, const void* x, const int32_t* topk_idx, int32_t* counts,
@@ -244,7 +250,7 @@ moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_
                            (const uint16_t*)W_up, pgu, (uint16_t*)h, s);
     if (e == hipSuccess)
         e = launch_down(*c, M, (const uint16_t*)h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn,
-                        (uint16_t*)y_perm, s);
+                        (uint16_t*)y_perm, nullptr, s);
     return hip_status(e);
 }
 
@@ -292,6 +298,15 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     const int M = moe_tile_m(c);
     int32_t* blocks = (int32_t*)((char*)hist + hist_bytes(c));
     int32_t* num_blocks = (int32_t*)((char*)blocks + schedule_bytes(c, M) - kAlign);
+    int32_t* arrive = (int32_t*)((char*)blocks + schedule_bytes(c, M));
+    // Fold the weighted combine into the down projection when its kernel can (packed weights, the
+    // per-block-regime kernels): the workgroup that writes the last of a token's k rows sums them.
+    // On request only (MOE_FLAG_FUSE_COMBINE; a test knob can force it either way): with one
+    // workgroup per CU nothing hides the latency of the epilogue's row reads, and from a few
+    // hundred rows on that costs more than the combine launch it saves.
+    const bool asked = knob(kKnobFuseCombine) >= 0 ? knob(kKnobFuseCombine) != 0 : (c->flags & MOE_FLAG_FUSE_COMBINE) != 0;
+    const bool fuse = asked && down_fuses_combine(*c, M, pdn != nullptr);
+    const CombineFusion fusion{src_of, row_of, topk_w, arrive, (uint16_t*)y};
 
     hipError_t e = hipSuccess;
     auto mark = [&](int i) {
@@ -299,7 +314,8 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     };
     mark(0);
     if (e == hipSuccess)
-        e = launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, route_ws, s);
+        e = launch_route(*c, (const uint16_t*)x, (const uint16_t*)W_r, bias, topk_idx, topk_w, route_ws,
+                         fuse ? arrive : nullptr, combine_groups(*c), s);
     mark(1);
     if (e == hipSuccess)
         e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);
@@ -311,9 +327,10 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
                            (const uint16_t*)W_gate, (const uint16_t*)W_up, pgu, h, s);
     mark(3);
     if (e == hipSuccess)
-        e = launch_down(*c, M, h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm, s);
+        e = launch_down(*c, M, h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm,
+                        fuse ? &fusion : nullptr, s);
     mark(4);
-    if (e == hipSuccess) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);
+    if (e == hipSuccess && !fuse) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);
     mark(5);
     return hip_status(e);
 }

@@ -42,6 +42,13 @@ int pick(int M, bool packed, const moe_config& c) {
 
 }  // namespace
 
+bool down_fuses_combine(const moe_config& c, int32_t M, bool packed) {
+    int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
+    if (id < 0) id = pick(M, packed, c);
+    // the per-block-regime kernels (LDS-DMA body) carry the fused epilogue; token * groups + group is an int
+    return id >= 5 && (long long)c.T * combine_groups(c) < (1ll << 31);
+}
+
 const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
     int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);
@@ -50,7 +57,7 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
-                       const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s) {
+                       const uint16_t* packed_dn, uint16_t* y_perm, const CombineFusion* fuse, hipStream_t s) {
     GemmArgs a{};
     a.X = h;
     a.src = nullptr;
@@ -76,6 +83,16 @@ hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_
     int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);
     if (kDown[id].M < M) return hipErrorInvalidValue;
+    if (fuse != nullptr) {
+        if (id < 5) return hipErrorInvalidValue;   // only the per-block-regime kernels have the fused epilogue
+        a.comb_src = fuse->src_of;
+        a.comb_row_of = fuse->row_of;
+        a.comb_w = fuse->topk_w;
+        a.comb_arrive = fuse->arrive;
+        a.comb_y = fuse->y;
+        a.comb_k = c.k;
+        a.comb_groups = combine_groups(c);
+    }
     return kDown[id].fn(a, moe_max_blocks(&c, M), s);
 }
 

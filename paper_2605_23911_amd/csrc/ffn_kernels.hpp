@@ -62,6 +62,14 @@ struct GemmArgs {
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
     int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
     int even;                   // tile_kernel_mixed: rows of a multi-tile expert dealt evenly over its schedule entries
+    int short_nt;               // tile_kernel_mixed: tiles of at most this many rows stream their weights non-temporally
+    // Weighted combine folded into the down projection (all null / 0 when it is a separate launch):
+    const int32_t* comb_src;    // [R] flat (token, slot) index of every expert-contiguous row
+    const int32_t* comb_row_of; // [T, k] expert-contiguous row of every (token, slot)
+    const float* comb_w;        // [T, k] gate weights
+    int32_t* comb_arrive;       // [T, comb_groups] rows of the token written so far per 128-feature group (zero at launch)
+    uint16_t* comb_y;           // [T, N] layer output
+    int comb_k, comb_groups;    // experts per token; ceil(N / 128)
 };
 
 typedef hipError_t (*launch_fn)(const GemmArgs&, int, hipStream_t);
@@ -226,7 +234,11 @@ __device__ __forceinline__ bool map_workgroup(const GemmArgs& a, int& tile, int&
 // = 0: features 0..7 and 16..23, lane/32 = 1: 8..15 and 24..31) instead of four 8-byte ones:
 // half as many store instructions and write requests.  Every lane of the wavefront must call
 // this (the swap is a cross-lane operation); `live` masks the stores of rows beyond the tile.
-template <bool GATEUP>
+// DEVICE_SCOPE: the 16-byte pieces are written with device-scope (sc1) stores, which go through
+// to the level all XCDs share, so that a workgroup on another XCD can read them after this
+// wavefront has waited for its stores and bumped a counter (fused combine), without an L2
+// write-back.
+template <bool GATEUP, bool DEVICE_SCOPE = false>
 __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, uint16_t* out_row, int f0, int half,
                                             int N, bool live) {
     uint2 pk[4];
@@ -247,7 +259,15 @@ __device__ __forceinline__ void store_block(const f32x16& g, const f32x16& u, ui
         const int f = f0 + (2 * p + half) * 8;
         const uint4 v = half ? make_uint4(got.x, got.y, pk[2 * p + 1].x, pk[2 * p + 1].y)
                              : make_uint4(pk[2 * p].x, pk[2 * p].y, got.x, got.y);
-        if (live && f < N) *reinterpret_cast<uint4*>(out_row + f) = v;
+        if (live && f < N) {
+            if constexpr (DEVICE_SCOPE) {
+                // one-row descriptor: base = the row, range = N elements
+                const u32x4 d4 = {v.x, v.y, v.z, v.w};
+                __builtin_amdgcn_raw_buffer_store_b128(d4, make_rsrc(out_row, (uint32_t)N * 2u), (uint32_t)f * 2u, 0, 16);
+            } else {
+                *reinterpret_cast<uint4*>(out_row + f) = v;
+            }
+        }
     }
 }
 
@@ -446,6 +466,92 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// Weighted combine (Eq. 3) folded into the down projection: the paper's limitation 1, second
+// half.  The k rows of a token come from k different experts, i.e. from workgroups that run at
+// different times on different XCDs, each with an L2 of its own.  A device-scope fence pair
+// (write back and invalidate the whole L2 around every tile) measured 1.4-2.7x on the down
+// projection; instead the tile of y_perm is written with device-scope stores, the wavefronts wait
+// for their acknowledgement, and the rows are read back with device-scope loads.  Each workgroup,
+// once its tile is written, adds 1 to a counter per (token, 128-feature group) for every row it
+// holds (device-scope atomics); whoever brings a counter to k knows that all k rows of that token and group are in
+// memory, reads them back and forms
+//     y[t, c] = sum_i w[t, i] * y_perm[row_of[t, i], c]
+// in fp32 in slot order i = 0..k-1 from the bf16 values in memory, its own row included: the
+// same arithmetic on the same operands as the stand-alone combine kernel, whichever workgroup
+// arrives last, so y is bit-reproducible and bit-equal to moe_combine's.  No workgroup ever waits
+// for another.  The counters are cleared by the router (the wavefront that routes token t clears
+// token t's counters), so no extra launch and no host-side reset is involved.
+// `nt` is the index of the workgroup's feature tile of width 128 * IB; xs is LDS that the
+// reduction loop no longer uses.
+template <int IB>
+__device__ __forceinline__ void fused_combine(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
+    int* list_n = reinterpret_cast<int*>(xs);
+    int* list = list_n + 4;            // up to rows * IB entries: token * groups + group
+    const int tid = threadIdx.x;
+    const int groups = a.comb_groups, k = a.comb_k;
+    wait_vmcnt<0>();                   // this wavefront's device-scope y_perm stores have been acknowledged
+    __syncthreads();                   // ... and so have the other wavefronts'; LDS is free (all LDS-DMAs have landed too)
+    if (tid == 0) *list_n = 0;
+    __syncthreads();
+    for (int r = tid; r < t.rows; r += kThreads) {
+        const int token = a.comb_src[t.row0 + r] / k;
+#pragma unroll
+        for (int ib = 0; ib < IB; ++ib) {
+            const int g = nt * IB + ib;
+            if (g < groups) {
+                const int old = atomicAdd(&a.comb_arrive[(size_t)token * groups + g], 1);
+                if (old == k - 1) list[atomicAdd(list_n, 1)] = token * groups + g;
+            }
+        }
+    }
+    __syncthreads();
+    const int n = *list_n;
+    if (n == 0) return;
+    const int sub = tid & 15;          // 16 lanes x 16 bytes = one 128-feature group of one row
+    const uint32_t row_bytes = (uint32_t)a.ldo * 2u;
+    const rsrc_t out_rows = make_rsrc(a.Out, (uint32_t)a.R * row_bytes);   // < 4 GiB: checked by the launcher
+    for (int q = tid >> 4; q < n; q += kThreads / 16) {
+        const int tg = list[q];
+        const int token = tg / groups, g = tg - token * groups;
+        const int c = g * 128 + sub * 8;
+        if (c >= a.N) continue;
+        const int32_t* rows = a.comb_row_of + (size_t)token * k;
+        const float* w = a.comb_w + (size_t)token * k;
+        float acc[8];
+#pragma unroll
+        for (int v = 0; v < 8; ++v) acc[v] = 0.0f;
+        // Eight rows are requested before the first is used (the workgroup has its CU to itself:
+        // nothing else hides the latency of these loads); the sum still runs in slot order.
+        for (int i0 = 0; i0 < k; i0 += 8) {
+            u32x4 v[8];
+            float wi[8];
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                const int i = i0 + b < k ? i0 + b : k - 1;
+                // device-scope (sc1) load: served from the level all XCDs share, never from a line this XCD cached earlier
+                v[b] = __builtin_amdgcn_raw_buffer_load_b128(out_rows, (uint32_t)rows[i] * row_bytes + (uint32_t)c * 2u, 0, 16);
+                wi[b] = w[i];
+            }
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                if (i0 + b < k) {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p) {
+                        acc[2 * p] = fmaf(wi[b], __uint_as_float(v[b][p] << 16), acc[2 * p]);
+                        acc[2 * p + 1] = fmaf(wi[b], __uint_as_float(v[b][p] & 0xffff0000u), acc[2 * p + 1]);
+                    }
+                }
+            }
+        }
+        uint4 o;
+        o.x = pack2_bf16(acc[0], acc[1]);
+        o.y = pack2_bf16(acc[2], acc[3]);
+        o.z = pack2_bf16(acc[4], acc[5]);
+        o.w = pack2_bf16(acc[6], acc[7]);
+        *reinterpret_cast<uint4*>(a.comb_y + (size_t)token * a.N + c) = o;
+    }
+}
+
 template <int JB, int JBE, int IB, bool GATEUP, int STAGES, int XD, bool PACKED, bool WNT = false>
 __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NM = GATEUP ? 2 : 1;
@@ -586,6 +692,19 @@ __device__ __forceinline__ void tile_body_dma(const GemmArgs& a, const Tile& t, 
     });
     wait_vmcnt<0>();   // nothing of this workgroup may still be writing LDS when it retires
 
+    if constexpr (!GATEUP) {
+        if (a.comb_arrive != nullptr) {
+            static_for<IB>([&](auto ib) {
+                static_for<JBE>([&](auto j) {
+                    const int tr = j * 32 + li;
+                    const bool live = tr < t.rows;
+                    store_block<GATEUP, true>(acc[ib][j], acc[ib][j], a.Out + (size_t)(t.row0 + (live ? tr : 0)) * a.ldo,
+                                              n0w + ib * 32, half, N, live);
+                });
+            });
+            return fused_combine<IB>(a, t, nt, xs);
+        }
+    }
     static_for<IB>([&](auto ib) {
         static_for<JBE>([&](auto j) {
             const int tr = j * 32 + li;
@@ -772,14 +891,19 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     t.rows = rows;
     t.n_e = n_e;
     GemmArgs b = a;
-    if (t.n_e > a.M) b.rot_mul = a.rot_mul_multi;
+    // A short last tile of a multi-tile expert runs through k several times faster than its
+    // siblings and shares nothing with them in time: it streams the panel like a single-block
+    // expert does (non-temporal, k rotated), so that its stream does not evict the panels the
+    // full tiles share.
+    const bool shared = t.n_e > a.M && t.rows > a.short_nt;
+    if (shared) b.rot_mul = a.rot_mul_multi;
     if constexpr (IB == 2 && !GATEUP) {
         if (halves) {
-            if (t.n_e > a.M) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
+            if (shared) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
             return dma_dispatch<1, GATEUP, PACKED, WNT>(b, t, nt, xs);
         }
     }
-    if (t.n_e > a.M) return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
+    if (shared) return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
     dma_dispatch<IB, GATEUP, PACKED, WNT>(b, t, nt, xs);
 }
 
@@ -942,6 +1066,7 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     args.sib = knob(kKnobSideBySide) >= 0 ? knob(kKnobSideBySide) : 1;
     args.even = knob(kKnobEvenRows) >= 0 ? knob(kKnobEvenRows) : (GATEUP ? 1 : 2);
     args.chunk = knob(kKnobXcdChunk) >= 0 ? knob(kKnobXcdChunk) : (!GATEUP && WNT ? 1 : 0);
+    args.short_nt = knob(kKnobShortNt) >= 0 ? knob(kKnobShortNt) : 0;
     args.rot_mul_multi = rot_steps(true);
     long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking
     args.slots = 0;

@@ -47,6 +47,8 @@ enum {
     kKnobEvenRows = 3,        // 0: Algorithm 1's row ranges everywhere, 3: every multi-tile expert dealt evenly
     kKnobXcdChunk = 4,        // 0/1: per-XCD contiguous chunks off/on for both projections
     kKnobRot = 5,             // k-loop rotation between the workgroups of an XCD, in steps
+    kKnobShortNt = 6,         // rows up to which a multi-tile expert's last tile streams its weights non-temporally
+    kKnobFuseCombine = 7,     // 0: moe_forward always launches the combine kernel, 1: folds it into the down projection whenever the kernel can
     kNumKnobs = 8
 };
 extern int g_knobs[kNumKnobs];
@@ -55,8 +57,11 @@ inline int knob(int i) { return g_knobs[i]; }
 // ---- launchers (each enqueues on `s` and returns hipGetLastError()) ----------------------
 // workspace: route_workspace_bytes(c) bytes of fp64 partial logit tiles
 size_t route_workspace_bytes(const moe_config& c);
+// zero / zero_per_token: if zero != nullptr the wavefront that routes token t also clears
+// zero[t * zero_per_token .. + zero_per_token) (the fused combine's arrival counters).
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s);
+                        int32_t* topk_idx, float* topk_w, void* workspace, int32_t* zero, int zero_per_token,
+                        hipStream_t s);
 
 // scratch: chunk histograms [nchunks, E] int32.  If blocks != nullptr the block schedule for
 // tile height M is emitted by the scan kernel as well.
@@ -80,9 +85,21 @@ hipError_t launch_gate_up(const moe_config& c, int32_t M, const uint16_t* x_rows
                           int32_t ldh, const int32_t* offsets,
                           const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wg,
                           const uint16_t* wu, const uint16_t* packed_gu, uint16_t* h, hipStream_t s);
+// Buffers of the weighted combine when it is folded into the down projection (Eq. 3 computed by
+// the workgroup that writes the last of a token's k rows); nullptr = separate combine launch.
+struct CombineFusion {
+    const int32_t* src_of;   // [R]
+    const int32_t* row_of;   // [T, k]
+    const float* topk_w;     // [T, k]
+    int32_t* arrive;         // [T, combine_groups(c)] int32, zero when the down projection starts
+    uint16_t* y;             // [T, d]
+};
+inline int combine_groups(const moe_config& c) { return (c.d + 127) / 128; }
+// whether the down-projection kernel chosen for this configuration can fold the combine in
+bool down_fuses_combine(const moe_config& c, int32_t M, bool packed);
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
                        const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
-                       const uint16_t* packed_dn, uint16_t* y_perm, hipStream_t s);
+                       const uint16_t* packed_dn, uint16_t* y_perm, const CombineFusion* fuse, hipStream_t s);
 
 const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed);
 const char* down_variant_name(const moe_config& c, int32_t M, bool packed);

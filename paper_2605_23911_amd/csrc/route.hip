@@ -133,6 +133,14 @@ __global__ __launch_bounds__(kThreads) void logits_kernel(const uint16_t* __rest
 // Sec. 3.4: max-subtracted softmax (or sigmoid), k rounds of arg-max over the logits with the
 // winners masked, ties to the lower index.
 constexpr int kLogitsPerLane = kMaxExperts / kWave;
+// moe_forward's down projection counts, per (token, 128-feature group), how many of the token's
+// k expert rows have been written (see ffn_kernels.hpp, fused_combine).  The counters of token t
+// are cleared here by the wavefront that routes t, so the layer needs no clearing launch.
+__device__ __forceinline__ void zero_token_counters(int32_t* __restrict__ zero, int zero_n, int t, int lane) {
+    if (zero == nullptr) return;
+    for (int i = lane; i < zero_n; i += kWave) zero[(size_t)t * zero_n + i] = 0;
+}
+
 __device__ __forceinline__ void gate_and_select(double (&z)[kLogitsPerLane], const bool (&ok)[kLogitsPerLane],
                                                 int lane, int wave, int t, int k, int gating,
                                                 double (*wsel)[kMaxExperts], int32_t (*sel_idx)[kMaxExperts],
@@ -208,12 +216,14 @@ __device__ __forceinline__ void gate_and_select(double (&z)[kLogitsPerLane], con
 __global__ __launch_bounds__(kThreads) void topk_kernel(const double* __restrict__ part,
                                                        const float* __restrict__ bias,
                                                        int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-                                                       int T, int E, int k, int gating, int T16, int E16, int KS) {
+                                                       int T, int E, int k, int gating, int T16, int E16, int KS,
+                                                       int32_t* __restrict__ zero, int zero_n) {
     __shared__ double wsel[kWavesPerBlock][kMaxExperts];
     __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
     const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
     const int t = blockIdx.x * kWavesPerBlock + wave;
     if (t >= T) return;
+    zero_token_counters(zero, zero_n, t, lane);
 
     constexpr int Q = kLogitsPerLane;
     const double ninf = -__builtin_huge_val();
@@ -253,7 +263,7 @@ __global__ __launch_bounds__(kThreads) void route_direct_kernel(const uint16_t* 
                                                                const float* __restrict__ bias,
                                                                int32_t* __restrict__ topk_idx,
                                                                float* __restrict__ topk_w, int d, int E, int k,
-                                                               int gating) {
+                                                               int gating, int32_t* __restrict__ zero, int zero_n) {
     __shared__ double wsel[kWavesPerBlock][kMaxExperts];
     __shared__ int32_t sel_idx[kWavesPerBlock][kMaxExperts];
     __shared__ double partial[kWavesPerBlock][EB];
@@ -299,6 +309,7 @@ __global__ __launch_bounds__(kThreads) void route_direct_kernel(const uint16_t* 
     }
     __syncthreads();
     if (wave != 0) return;
+    zero_token_counters(zero, zero_n, t, lane);
     constexpr int Q = kLogitsPerLane;
     double z[Q];
     bool ok[Q];
@@ -347,11 +358,11 @@ size_t route_workspace_bytes(const moe_config& c) {
 }
 
 hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* wr, const float* bias,
-                        int32_t* topk_idx, float* topk_w, void* workspace, hipStream_t s) {
+                        int32_t* topk_idx, float* topk_w, void* workspace, int32_t* zero, int zero_per_token, hipStream_t s) {
     if (c.E <= 8 && c.T <= 2048) {   // measured: with 16 experts or more tokens the MFMA path is faster
         const dim3 g(c.T);
         hipLaunchKernelGGL(route_direct_kernel<8>, g, dim3(kThreads), 0, s, x, wr, bias, topk_idx, topk_w, c.d, c.E,
-                           c.k, c.gating);
+                           c.k, c.gating, zero, zero_per_token);
         return hipGetLastError();
     }
     const RoutePlan p = plan(c);
@@ -365,7 +376,7 @@ hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* 
         hipLaunchKernelGGL(logits_kernel<1>, grid, dim3(kThreads), 0, s, x, wr, part, c.T, c.d, c.E, p.T16, p.E16,
                            p.KS, units);
     hipLaunchKernelGGL(topk_kernel, dim3((c.T + kWavesPerBlock - 1) / kWavesPerBlock), dim3(kThreads), 0, s, part,
-                       bias, topk_idx, topk_w, c.T, c.E, c.k, c.gating, p.T16, p.E16, p.KS);
+                       bias, topk_idx, topk_w, c.T, c.E, c.k, c.gating, p.T16, p.E16, p.KS, zero, zero_per_token);
     return hipGetLastError();
 }
 

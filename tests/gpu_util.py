@@ -73,9 +73,9 @@ class Layer:
         self.bank = bank
         self.wg, self.wu, self.wd, self.packed = bank.wg, bank.wu, bank.wd, bank.packed
 
-    def cfg(self, tile_m: int = 0, T: int | None = None):
+    def cfg(self, tile_m: int = 0, T: int | None = None, flags: int = 0):
         s = self.shape
-        return moe.MoEConfig.of(s.T if T is None else T, s.d, s.F, s.E, s.k, s.gating, tile_m)
+        return moe.MoEConfig.of(s.T if T is None else T, s.d, s.F, s.E, s.k, s.gating, tile_m, flags)
 
     def expert_bits(self, e: int):
         return self.bank.expert_bits(e)
@@ -93,10 +93,10 @@ class Layer:
         return None if self.bias_cpu is None else self.bias_cpu.numpy()
 
 
-def run_forward(layer: Layer, tile_m: int = 0, packed: bool = True):
+def run_forward(layer: Layer, tile_m: int = 0, packed: bool = True, flags: int = 0):
     """moe_forward through the C ABI; returns y bits and every intermediate from the workspace.
     packed=True hands the kernels the pre-packed weight copy only (row-major pointers NULL)."""
-    cfg = layer.cfg(tile_m)
+    cfg = layer.cfg(tile_m, flags=flags)
     s = layer.shape
     lay = moe.forward_workspace_layout(cfg)
     ws = torch.zeros(lay.total, dtype=torch.uint8, device=DEV)

@@ -39,10 +39,13 @@ def test_status_strings(L):
 def test_config_validation(L):
     ok = moe.MoEConfig.of(64, 256, 512, 8, 2)
     assert moe.tile_m(ok) == 256 and moe.forward_workspace_size(ok) > 0
+    assert moe.workspace_size(ok) == moe.forward_workspace_size(ok)
+    assert moe.forward_workspace_size(moe.MoEConfig.of(64, 256, 512, 8, 2, flags=moe.FLAG_FUSE_COMBINE)) > 0
     bad = [moe.MoEConfig.of(-1, 256, 512, 8, 2), moe.MoEConfig.of(4, 256, 512, 8, 9),
            moe.MoEConfig.of(4, 256, 512, 8, 0), moe.MoEConfig.of(4, 256, 512, 257, 2),
            moe.MoEConfig.of(4, 250, 512, 8, 2), moe.MoEConfig.of(4, 256, 500, 8, 2),
-           moe.MoEConfig.of(4, 256, 512, 8, 2, gating=7), moe.MoEConfig.of(4, 256, 512, 8, 2, tile_m=48)]
+           moe.MoEConfig.of(4, 256, 512, 8, 2, gating=7), moe.MoEConfig.of(4, 256, 512, 8, 2, tile_m=48),
+           moe.MoEConfig.of(4, 256, 512, 8, 2, flags=2)]
     for c in bad:
         assert moe.tile_m(c) == 0 and moe.forward_workspace_size(c) == 0
         assert moe.permute_workspace_size(c) == 0 and moe.ffn_workspace_size(c) == 0

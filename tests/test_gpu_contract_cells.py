@@ -144,6 +144,12 @@ def _cell(G, preset, T, skew, n_y):
         assert e_h2 <= REL and e_v2 <= REL, (e, e_h2, e_v2)
         n_rows += len(rr)
         worst = max(worst, e_h2, e_v2)
+    if (preset, T, skew) in _FUSED_TOO:
+        import paper_2605_23911_amd as moe
+        _say(f"{preset} T={T} skew={skew}: again with the combine folded into the down projection")
+        fused = G.run_forward(layer, flags=moe.FLAG_FUSE_COMBINE)
+        for key in ("h", "y_perm", "y"):
+            assert np.array_equal(out[key], fused[key]), key
     _say(f"{preset} T={T} skew={skew}: {int((counts > 0).sum())} active experts, fullest {int(counts[hot])} rows, "
          f"emptiest {int(counts[cold])}; {n_rows} rows checked, worst rel err {worst:.2e}, y {e_y:.2e}")
 
@@ -158,6 +164,12 @@ _CELLS = (
     + [("dsv3", T, s, 2) for T in (512, 4096) for s in (0.0, 1.0, 1.5, 2.0)]
     + [("mixtral22", 512, 0.0, 2), ("ladder128", 512, 0.0, 2)]
 )
+
+
+# cells that are also run with MOE_FLAG_FUSE_COMBINE: y (and h, y_perm) must be bit-equal to the
+# separate combine launch, whatever the arrival order of the workgroups was
+_FUSED_TOO = {("mixtral", 16, 0.0), ("mixtral", 512, 0.0), ("mixtral", 4096, 0.0), ("qwen2moe", 4096, 1.0),
+              ("dsv3", 64, 0.0), ("dsv3", 4096, 2.0)}
 
 
 def test_mixtral_T512_row_major_weights(G):

@@ -307,6 +307,28 @@ def test_multi_tile_experts_all_rows(G, knobs, name):
         _all_rows_against_oracle(G, layer, ref, other)
 
 
+@pytest.mark.parametrize("shape,skew", [(("ragged", 333, 192, 320, 7, 3), 2.0), (("wide", 700, 512, 256, 16, 4), 1.0),
+                                        (("five_tiles", 1100, 2048, 1024, 2, 2), 0.0), (("e256", 300, 256, 192, 256, 8), 0.0)])
+def test_combine_folded_into_the_down_projection(G, shape, skew):
+    """moe_forward lets the down-projection workgroup that writes the last of a token's k rows
+    form y (no separate combine launch).  The sum is taken in slot order from the bf16 rows in
+    memory whoever arrives last, so y must be bit-equal to the separate combine kernel's (knob 0),
+    identical from run to run, and within tolerance of the oracle."""
+    s = mi.MoEShape(*shape, mi.GATE_SOFTMAX_RENORM)
+    layer = G.Layer(s, seed=9, skew=skew)
+    ref = _oracle_full(layer)
+    import paper_2605_23911_amd as moe
+    _say(f"{s.name}: combine folded into the down projection (MOE_FLAG_FUSE_COMBINE)")
+    fused = [G.run_forward(layer, flags=moe.FLAG_FUSE_COMBINE) for _ in range(3)]
+    _say(f"{s.name}: separate combine launch")
+    plain = G.run_forward(layer)
+    _check_routing(fused[0], ref, layer)
+    _check_floats(fused[0], ref, layer, G)
+    for out in fused:
+        for key in ("h", "y_perm", "y"):
+            assert np.array_equal(out[key], plain[key]), key
+
+
 def test_down_projection_variants_and_graph_replay(G, knobs):
     """Every packed down-projection kernel forced onto the ragged shape (the selection rules
     would pick only one of them at this size) against the oracle, and a HIP-graph capture of
@@ -325,30 +347,32 @@ def test_down_projection_variants_and_graph_replay(G, knobs):
         out = G.run_forward(layer)
         _all_rows_against_oracle(G, layer, ref, out)
     knobs(B.KNOB_DOWN_VARIANT, -1)
-    _say("graph capture + replays of the default path")
-    lay = moe.forward_workspace_layout(cfg)
-    ws = torch.zeros(lay.total, dtype=torch.uint8, device=G.DEV)
-    y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=G.DEV)
-    run = lambda: moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, None, None, None, y, ws, W_packed=layer.packed)
-    run()
-    torch.cuda.synchronize()
-    y_eager = y.clone()
-    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
-    with torch.cuda.stream(side):
+    for flags, label in [(0, "default path"), (moe.FLAG_FUSE_COMBINE, "combine folded into the down projection")]:
+        _say(f"graph capture + replays: {label}")
+        cfg = layer.cfg(flags=flags)
+        lay = moe.forward_workspace_layout(cfg)
+        ws = torch.zeros(lay.total, dtype=torch.uint8, device=G.DEV)
+        y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=G.DEV)
+        run = lambda: moe.moe_forward(cfg, layer.x, layer.wr, layer.bias, None, None, None, y, ws, W_packed=layer.packed)
         run()
         torch.cuda.synchronize()
-        with torch.cuda.graph(graph, stream=side):
+        y_eager = y.clone()
+        graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+        with torch.cuda.stream(side):
             run()
-    for _ in range(3):
-        y.zero_()
-        ws.zero_()
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        assert torch.equal(y, y_eager)
-        run()                      # eager work between the replays
-        torch.cuda.synchronize()
-        assert torch.equal(y, y_eager)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                run()
+        for _ in range(3):
+            y.zero_()
+            ws.fill_(0xff if flags else 0)   # the layer must clear its own arrival counters
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(y, y_eager)
+            run()                      # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(y, y_eager)
 
 
 def test_zero_tokens_is_a_noop(G):
