@@ -279,8 +279,8 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
         misaligned(y) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)) != 0 ||
         (reinterpret_cast<uintptr_t>(W_packed) & (kAlign - 1)) != 0)
         return MOE_ERR_ALIGN;
+    if (c->T == 0) return MOE_OK;   // nothing to do, so no workspace is needed either
     if (ws_bytes < l.total) return MOE_ERR_WORKSPACE;
-    if (c->T == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)stream;
     char* ws = (char*)workspace;
     const uint16_t* pgu = (const uint16_t*)W_packed;

@@ -1066,7 +1066,7 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     args.sib = knob(kKnobSideBySide) >= 0 ? knob(kKnobSideBySide) : 1;
     args.even = knob(kKnobEvenRows) >= 0 ? knob(kKnobEvenRows) : (GATEUP ? 1 : 2);
     args.chunk = knob(kKnobXcdChunk) >= 0 ? knob(kKnobXcdChunk) : (!GATEUP && WNT ? 1 : 0);
-    args.short_nt = knob(kKnobShortNt) >= 0 ? knob(kKnobShortNt) : 0;
+    args.short_nt = knob(kKnobShortNt) >= 0 ? knob(kKnobShortNt) : (GATEUP ? 64 : 0);
     args.rot_mul_multi = rot_steps(true);
     long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking
     args.slots = 0;
