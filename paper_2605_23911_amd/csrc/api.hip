@@ -5,7 +5,7 @@
 #include "moe_internal.hpp"
 
 namespace moe {
-int g_knobs[kNumKnobs] = {-1, -1, -1, -1, -1, -1, -1, -1};
+int g_knobs[kNumKnobs] = {-1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1, -1};
 }
 
 namespace {
@@ -41,9 +41,10 @@ moe_status check_config(const moe_config* c) {
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-size_t schedule_bytes(const moe_config* c, int M) {
-    return align_up((size_t)moe_max_blocks(c, M) * 2 * sizeof(int32_t)) + kAlign;   // + num_blocks
-}
+size_t list_bytes(const moe_config* c, int M) { return align_up((size_t)moe_max_blocks(c, M) * 2 * sizeof(int32_t)); }
+// Algorithm 1's block list, the same blocks with the multi-block experts first (for the down
+// projection, see permute.hip), and one 256-byte slot holding num_blocks and num_heavy.
+size_t schedule_bytes(const moe_config* c, int M) { return 2 * list_bytes(c, M) + kAlign; }
 
 size_t arrive_bytes(const moe_config* c) {
     return align_up((size_t)(c->T > 0 ? c->T : 1) * combine_groups(*c) * sizeof(int32_t));
@@ -174,7 +175,7 @@ moe_status moe_permute(const moe_config* c, const void* x, const int32_t* topk_i
     if (c->T == 0) return MOE_OK;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, (int32_t*)workspace, 0,
-                                        nullptr, nullptr, s);
+                                        nullptr, nullptr, nullptr, nullptr, s);
     if (e == hipSuccess && x != nullptr && c->T > 0)
         e = launch_gather_rows(*c, (const uint16_t*)x, src_of, (uint16_t*)x_perm, c->d, s);
     return hip_status(e);
@@ -194,7 +195,7 @@ moe_status moe_permute_static(const moe_config* c, const void* x, const int32_t*
     hipError_t e = permute_static_scratch(&hist);
     hipStream_t s = (hipStream_t)stream;
     if (e == hipSuccess)
-        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, 0, nullptr, nullptr, s);
+        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, 0, nullptr, nullptr, nullptr, nullptr, s);
     if (e == hipSuccess && x != nullptr)
         e = launch_gather_rows(*c, (const uint16_t*)x, src_of, (uint16_t*)x_perm, c->d, s);
     return hip_status(e);
@@ -207,7 +208,7 @@ moe_status moe_block_schedule(const moe_config* c, const int32_t* offsets, int32
     if (M < 1 || M > (1 << 30)) return MOE_ERR_SHAPE;   // ceil(n_e / M) is computed as (n_e + M - 1) / M in 32 bits
     if (!offsets || !blocks || !num_blocks) return MOE_ERR_NULL;
     if (c->T == 0) return MOE_OK;
-    return hip_status(launch_block_schedule(*c, offsets, M, blocks, num_blocks, (hipStream_t)stream));
+    return hip_status(launch_block_schedule(*c, offsets, M, blocks, num_blocks, nullptr, nullptr, (hipStream_t)stream));
 }
 
 size_t moe_packed_weights_size(const moe_config* c) {
@@ -241,15 +242,17 @@ moe_status moe_grouped_ffn(const moe_config* c, const void* x_perm, const int32_
     hipStream_t s = (hipStream_t)stream;
     const int M = moe_tile_m(c);
     int32_t* blocks = (int32_t*)workspace;
+    int32_t* blocks_mix = (int32_t*)((char*)workspace + list_bytes(c, M));
     int32_t* num_blocks = (int32_t*)((char*)workspace + schedule_bytes(c, M) - kAlign);
+    int32_t* num_heavy = num_blocks + 1;
     const uint16_t* pgu = (const uint16_t*)W_packed;
     const uint16_t* pdn = pgu ? pgu + packed_gate_up_bytes(*c) / sizeof(uint16_t) : nullptr;
-    hipError_t e = launch_block_schedule(*c, offsets, M, blocks, num_blocks, s);
+    hipError_t e = launch_block_schedule(*c, offsets, M, blocks, num_blocks, blocks_mix, num_heavy, s);
     if (e == hipSuccess)
         e = launch_gate_up(*c, M, (const uint16_t*)x_perm, c->d, nullptr, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_gate,
                            (const uint16_t*)W_up, pgu, (uint16_t*)h, s);
     if (e == hipSuccess)
-        e = launch_down(*c, M, (const uint16_t*)h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn,
+        e = launch_down(*c, M, (const uint16_t*)h, c->F, offsets, blocks, num_blocks, blocks_mix, num_heavy, (const uint16_t*)W_down, pdn,
                         (uint16_t*)y_perm, nullptr, s);
     return hip_status(e);
 }
@@ -297,7 +300,9 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
     int32_t* hist = (int32_t*)(ws + l.scratch + moe_route_workspace_size(c));
     const int M = moe_tile_m(c);
     int32_t* blocks = (int32_t*)((char*)hist + hist_bytes(c));
+    int32_t* blocks_mix = (int32_t*)((char*)blocks + list_bytes(c, M));
     int32_t* num_blocks = (int32_t*)((char*)blocks + schedule_bytes(c, M) - kAlign);
+    int32_t* num_heavy = num_blocks + 1;
     int32_t* arrive = (int32_t*)((char*)blocks + schedule_bytes(c, M));
     // Fold the weighted combine into the down projection when its kernel can (packed weights, the
     // per-block-regime kernels): the workgroup that writes the last of a token's k rows sums them.
@@ -318,7 +323,7 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
                          fuse ? arrive : nullptr, combine_groups(*c), s);
     mark(1);
     if (e == hipSuccess)
-        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, s);
+        e = launch_permute_index(*c, topk_idx, counts, offsets, row_of, src_of, hist, M, blocks, num_blocks, blocks_mix, num_heavy, s);
     mark(2);
     // The row gather of the permutation is folded into the gate+up tile loads (row r is read from
     // x[src_of[r] / k]); the permuted copy of x that moe_permute can write is not needed here.
@@ -327,7 +332,7 @@ moe_status moe_forward_staged(const moe_config* c, const void* x, const void* W_
                            (const uint16_t*)W_gate, (const uint16_t*)W_up, pgu, h, s);
     mark(3);
     if (e == hipSuccess)
-        e = launch_down(*c, M, h, c->F, offsets, blocks, num_blocks, (const uint16_t*)W_down, pdn, y_perm,
+        e = launch_down(*c, M, h, c->F, offsets, blocks, num_blocks, blocks_mix, num_heavy, (const uint16_t*)W_down, pdn, y_perm,
                         fuse ? &fusion : nullptr, s);
     mark(4);
     if (e == hipSuccess && !fuse) e = launch_combine(*c, y_perm, row_of, topk_w, (uint16_t*)y, s);

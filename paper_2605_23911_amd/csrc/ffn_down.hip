@@ -56,7 +56,8 @@ const char* down_variant_name(const moe_config& c, int32_t M, bool packed) {
 }
 
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
-                       const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
+                       const int32_t* blocks, const int32_t* num_blocks, const int32_t* blocks_mix,
+                       const int32_t* num_heavy, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, const CombineFusion* fuse, hipStream_t s) {
     GemmArgs a{};
     a.X = h;
@@ -83,6 +84,13 @@ hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_
     int id = forced_variant(kKnobDownVariant, kNumDown, M, packed, kDown);
     if (id < 0) id = pick(M, packed, c);
     if (kDown[id].M < M) return hipErrorInvalidValue;
+    // The two-weight-block kernel with cached loads (the choice once experts hold many rows, i.e.
+    // whenever routing skew has produced multi-block experts in a large batch) reads the list
+    // that holds the heavy blocks first and deals the two classes evenly over its launch.
+    if (id == 7 && blocks_mix != nullptr && num_heavy != nullptr && knob(kKnobInterleave) != 0) {
+        a.blocks = blocks_mix;
+        a.num_heavy = num_heavy;
+    }
     if (fuse != nullptr) {
         if (id < 5) return hipErrorInvalidValue;   // only the per-block-regime kernels have the fused epilogue
         a.comb_src = fuse->src_of;

@@ -57,11 +57,13 @@ struct GemmArgs {
     const int32_t* offsets;     // [E+1]
     const int32_t* blocks;      // [*, 2] (expert, row offset inside the expert)
     const int32_t* num_blocks;  // device scalar
+    const int32_t* num_heavy;   // device scalar or null: the first *num_heavy blocks belong to multi-block experts (tile_kernel_mixed)
     int R, N, K, n_tiles_n;
     int M;                      // tile height of the block schedule (rows per block <= M)
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
     int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
     int even;                   // tile_kernel_mixed: rows of a multi-tile expert dealt evenly over its schedule entries
+    int no_nt;                  // tile_kernel_mixed: cached weight loads for every block (test knob)
     int short_nt;               // tile_kernel_mixed: tiles of at most this many rows stream their weights non-temporally
     // Weighted combine folded into the down projection (all null / 0 when it is a separate launch):
     const int32_t* comb_src;    // [R] flat (token, slot) index of every expert-contiguous row
@@ -818,6 +820,29 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
             chunked = true;
         }
         if (w >= total) return;
+        // Heavy and light blocks dealt evenly over the launch.  With a.num_heavy the block list
+        // holds the blocks of multi-block experts first (their workgroups are bound by the matrix
+        // cores and leave HBM mostly alone), then the single-block experts (bound by the weight
+        // stream).  Launched in that order, or in expert order under routing skew, the chip runs
+        // stretches of one kind only: all CUs compute while HBM idles, then all CUs stream and
+        // share the bandwidth.  Position p of the launch therefore takes the next unit of the
+        // class that a proportional (Bresenham) merge puts there, so that at any time the resident
+        // workgroups are a mix in the launch's own proportion: the streaming ones then have the
+        // memory system to themselves.  The unit is 8 consecutive ids where the feature-tile count
+        // is a multiple of 8 (id % 8, the XCD, and the side-by-side order below are kept), else
+        // one block.  Both classes keep their ascending expert order, so the light experts' weights
+        // are still read in address order.  Uniform routing has one class only: nothing moves.
+        if (a.num_heavy != nullptr && !chunked && !split_round) {
+            const int U = (a.n_tiles_n & 7) == 0 ? 8 : a.n_tiles_n;
+            const int hu = *a.num_heavy * a.n_tiles_n / U, tu = total / U, lu = tu - hu;
+            if (hu > 0 && lu > 0) {
+                const int p = w / U, r = w - p * U;
+                // heavy units among positions [0, p): floor(p * hu / tu); position p is heavy iff that count steps at p
+                const long long before = (long long)p * hu / tu, upto = (long long)(p + 1) * hu / tu;
+                const int unit = upto > before ? (int)before : hu + (p - (int)before);
+                w = unit * U + r;
+            }
+        }
         tile = w / a.n_tiles_n;
         nt = w - tile * a.n_tiles_n;
         if (halves) nt = 2 * nt + sub;   // index of the 128-feature tile the IB = 1 body works on
@@ -895,8 +920,9 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     // siblings and shares nothing with them in time: it streams the panel like a single-block
     // expert does (non-temporal, k rotated), so that its stream does not evict the panels the
     // full tiles share.
-    const bool shared = t.n_e > a.M && t.rows > a.short_nt;
-    if (shared) b.rot_mul = a.rot_mul_multi;
+    const bool multi = t.n_e > a.M && t.rows > a.short_nt;
+    if (multi) b.rot_mul = a.rot_mul_multi;
+    const bool shared = multi || a.no_nt;
     if constexpr (IB == 2 && !GATEUP) {
         if (halves) {
             if (shared) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
@@ -1066,6 +1092,7 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     args.sib = knob(kKnobSideBySide) >= 0 ? knob(kKnobSideBySide) : 1;
     args.even = knob(kKnobEvenRows) >= 0 ? knob(kKnobEvenRows) : (GATEUP ? 1 : 2);
     args.chunk = knob(kKnobXcdChunk) >= 0 ? knob(kKnobXcdChunk) : (!GATEUP && WNT ? 1 : 0);
+    args.no_nt = knob(kKnobNoNt) > 0;
     args.short_nt = knob(kKnobShortNt) >= 0 ? knob(kKnobShortNt) : (GATEUP ? 64 : 0);
     args.rot_mul_multi = rot_steps(true);
     long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking

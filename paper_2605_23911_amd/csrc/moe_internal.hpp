@@ -49,7 +49,9 @@ enum {
     kKnobRot = 5,             // k-loop rotation between the workgroups of an XCD, in steps
     kKnobShortNt = 6,         // rows up to which a multi-tile expert's last tile streams its weights non-temporally
     kKnobFuseCombine = 7,     // 0: moe_forward always launches the combine kernel, 1: folds it into the down projection whenever the kernel can
-    kNumKnobs = 8
+    kKnobInterleave = 8,      // 0: launch order = block order (no dealing of heavy and light blocks over the launch)
+    kKnobNoNt = 9,            // 1: cached weight loads for single-block experts too
+    kNumKnobs = 12
 };
 extern int g_knobs[kNumKnobs];
 inline int knob(int i) { return g_knobs[i]; }
@@ -65,16 +67,20 @@ hipError_t launch_route(const moe_config& c, const uint16_t* x, const uint16_t* 
 
 // scratch: chunk histograms [nchunks, E] int32.  If blocks != nullptr the block schedule for
 // tile height M is emitted by the scan kernel as well.
+// blocks_mix / num_heavy (may both be null): a second list of the same blocks, as a stable
+// partition into the blocks of multi-block experts and the rest, with *num_heavy (device int32) =
+// size of the first class (see emit_block_schedule in permute.hip; used by the down projection).
 hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
-                                int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s);
+                                int32_t M, int32_t* blocks, int32_t* num_blocks, int32_t* blocks_mix, int32_t* num_heavy,
+                                hipStream_t s);
 // Device address of the current GPU's file-scope scratch array (MOE_PERMUTE_STATIC_MAX_INTS
 // int32) that moe_permute_static hands to launch_permute_index in place of a caller workspace.
 hipError_t permute_static_scratch(int32_t** ptr);
 hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int32_t* src_of,
                               uint16_t* x_perm, int32_t ld_perm, hipStream_t s);
 hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M,
-                                 int32_t* blocks, int32_t* num_blocks, hipStream_t s);
+                                 int32_t* blocks, int32_t* num_blocks, int32_t* blocks_mix, int32_t* num_heavy, hipStream_t s);
 
 // packed_gu / packed_dn: the projection's region of moe_pack_weights' buffer, or nullptr to
 // read the row-major weights.  gate+up reads expert-contiguous rows x_rows[R, d] when src_of is
@@ -98,7 +104,8 @@ inline int combine_groups(const moe_config& c) { return (c.d + 127) / 128; }
 // whether the down-projection kernel chosen for this configuration can fold the combine in
 bool down_fuses_combine(const moe_config& c, int32_t M, bool packed);
 hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_t ldh, const int32_t* offsets,
-                       const int32_t* blocks, const int32_t* num_blocks, const uint16_t* wd,
+                       const int32_t* blocks, const int32_t* num_blocks, const int32_t* blocks_mix,
+                       const int32_t* num_heavy, const uint16_t* wd,
                        const uint16_t* packed_dn, uint16_t* y_perm, const CombineFusion* fuse, hipStream_t s);
 
 const char* gate_up_variant_name(const moe_config& c, int32_t M, bool packed);

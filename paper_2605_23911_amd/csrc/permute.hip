@@ -58,10 +58,29 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int* t
     return base + inc - v;
 }
 
+// Owner of block q in a list where expert e's blocks start at first[e] (non-decreasing in e):
+// the last expert whose first block index is <= q (experts that contribute no block share a
+// start with their successor, so the last one is the owner).
+__device__ __forceinline__ int owner_of_block(const int* first, int n, int q) {
+    int lo = 0, hi = n - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (first[mid] <= q) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
 // Algorithm 1: expert e contributes ceil(n_e / M) blocks (e, b*M), experts in ascending order.
 // Runs on one 256-thread workgroup; `n_e` is this thread's expert count (0 for tid >= E).
+// blocks_mix != nullptr asks for a second list with the same blocks as a stable partition: first
+// those of the experts that span several blocks (n_e > M, "heavy": their workgroups are bound by
+// the matrix cores), then the others ("light": bound by the weight stream), each class in
+// ascending expert order; *num_heavy = blocks of the first class.  The down projection deals the
+// two classes evenly over its launch (see tile_kernel_mixed).
 __device__ __forceinline__ void emit_block_schedule(int n_e, int M, int32_t* __restrict__ blocks,
-                                                    int32_t* __restrict__ num_blocks, int* first,
+                                                    int32_t* __restrict__ num_blocks,
+                                                    int32_t* __restrict__ blocks_mix,
+                                                    int32_t* __restrict__ num_heavy, int* first, int* first2,
                                                     int* wave_tot, int* total) {
     const int tid = threadIdx.x;
     const int nb = (n_e + M - 1) / M;
@@ -71,15 +90,32 @@ __device__ __forceinline__ void emit_block_schedule(int n_e, int M, int32_t* __r
     const int nblk = *total;
     if (tid == 0) *num_blocks = nblk;
     for (int q = tid; q < nblk; q += kThreads) {
-        // last expert whose first block index is <= q (experts with no rows share a start
-        // with their successor, so the last one is the owner)
-        int lo = 0, hi = kThreads - 1;
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (first[mid] <= q) lo = mid; else hi = mid - 1;
+        const int e = owner_of_block(first, kThreads, q);
+        blocks[2 * q] = e;
+        blocks[2 * q + 1] = (q - first[e]) * M;
+    }
+    if (blocks_mix == nullptr) return;
+    __syncthreads();
+    const bool heavy = nb > 1;
+    const int excl_h = block_exclusive_scan(heavy ? nb : 0, wave_tot, total);
+    const int n_heavy = *total;
+    __syncthreads();
+    const int excl_l = block_exclusive_scan(heavy ? 0 : nb, wave_tot, total);
+    first[tid] = excl_h;
+    first2[tid] = excl_l;
+    __syncthreads();
+    if (tid == 0) *num_heavy = n_heavy;
+    for (int q = tid; q < nblk; q += kThreads) {
+        int e, b;
+        if (q < n_heavy) {
+            e = owner_of_block(first, kThreads, q);
+            b = q - first[e];
+        } else {
+            e = owner_of_block(first2, kThreads, q - n_heavy);
+            b = q - n_heavy - first2[e];
         }
-        blocks[2 * q] = lo;
-        blocks[2 * q + 1] = (q - first[lo]) * M;
+        blocks_mix[2 * q] = e;
+        blocks_mix[2 * q + 1] = b * M;
     }
 }
 
@@ -89,10 +125,12 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(int32_t* __restrict__ ch
                                                        int R, int32_t* __restrict__ counts,
                                                        int32_t* __restrict__ offsets, int M,
                                                        int32_t* __restrict__ blocks,
-                                                       int32_t* __restrict__ num_blocks) {
+                                                       int32_t* __restrict__ num_blocks,
+                                                       int32_t* __restrict__ blocks_mix,
+                                                       int32_t* __restrict__ num_heavy) {
     __shared__ int wave_tot[kWaves];
     __shared__ int total;
-    __shared__ int first[kThreads];
+    __shared__ int first[kThreads], first2[kThreads];
     const int tid = threadIdx.x;
     int n_e = 0;
     if (tid < E)
@@ -111,19 +149,21 @@ __global__ __launch_bounds__(kThreads) void scan_kernel(int32_t* __restrict__ ch
     if (tid == 0) offsets[E] = R;
     if (blocks != nullptr) {
         __syncthreads();
-        emit_block_schedule(n_e, M, blocks, num_blocks, first, wave_tot, &total);
+        emit_block_schedule(n_e, M, blocks, num_blocks, blocks_mix, num_heavy, first, first2, wave_tot, &total);
     }
 }
 
 __global__ __launch_bounds__(kThreads) void schedule_kernel(const int32_t* __restrict__ offsets, int E, int M,
                                                            int32_t* __restrict__ blocks,
-                                                           int32_t* __restrict__ num_blocks) {
+                                                           int32_t* __restrict__ num_blocks,
+                                                           int32_t* __restrict__ blocks_mix,
+                                                           int32_t* __restrict__ num_heavy) {
     __shared__ int wave_tot[kWaves];
     __shared__ int total;
-    __shared__ int first[kThreads];
+    __shared__ int first[kThreads], first2[kThreads];
     const int tid = threadIdx.x;
     const int n_e = tid < E ? offsets[tid + 1] - offsets[tid] : 0;
-    emit_block_schedule(n_e, M, blocks, num_blocks, first, wave_tot, &total);
+    emit_block_schedule(n_e, M, blocks, num_blocks, blocks_mix, num_heavy, first, first2, wave_tot, &total);
 }
 
 // ---- 3. stable rank -----------------------------------------------------------------------
@@ -211,10 +251,11 @@ __device__ __forceinline__ void wave0_scan256(const int* v, int* out, int* total
 __global__ __launch_bounds__(kFusedThreads) void fused_permute_kernel(
     const int32_t* __restrict__ topk_idx, int R, int E, int32_t* __restrict__ counts, int32_t* __restrict__ offsets,
     int32_t* __restrict__ row_of, int32_t* __restrict__ src_of, int M, int32_t* __restrict__ blocks,
-    int32_t* __restrict__ num_blocks) {
+    int32_t* __restrict__ num_blocks, int32_t* __restrict__ blocks_mix, int32_t* __restrict__ num_heavy) {
     __shared__ int32_t wcnt[kFusedWaves][kMaxExperts];
     __shared__ int cnt[kMaxExperts], off[kMaxExperts], nb[kMaxExperts], first[kMaxExperts];
-    __shared__ int total_rows, total_blocks;
+    __shared__ int nbh[kMaxExperts], firsth[kMaxExperts], nbl[kMaxExperts], firstl[kMaxExperts];
+    __shared__ int total_rows, total_blocks, total_heavy, total_light;
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const int G = (R + kFusedWaves * kWave - 1) / (kFusedWaves * kWave);   // 64-slot groups per wavefront
     const int jw = wave * G * kWave;
@@ -234,12 +275,21 @@ __global__ __launch_bounds__(kFusedThreads) void fused_permute_kernel(
         if (tid < E)
             for (int w = 0; w < kFusedWaves; ++w) n += wcnt[w][tid];
         cnt[tid] = n;
-        nb[tid] = (n + M - 1) / M;
+        // block counts per expert: all (Algorithm 1's list), and split by class for the second
+        // list (see emit_block_schedule): multi-block experts in nbh, the others in nbl
+        const int b = (n + M - 1) / M;
+        nb[tid] = b;
+        nbh[tid] = b > 1 ? b : 0;
+        nbl[tid] = b > 1 ? 0 : b;
     }
     __syncthreads();
     if (wave == 0) {
         wave0_scan256(cnt, off, &total_rows, lane);
         wave0_scan256(nb, first, &total_blocks, lane);
+        if (blocks_mix != nullptr) {
+            wave0_scan256(nbh, firsth, &total_heavy, lane);
+            wave0_scan256(nbl, firstl, &total_light, lane);
+        }
     }
     __syncthreads();
     if (tid < E) {
@@ -253,17 +303,29 @@ __global__ __launch_bounds__(kFusedThreads) void fused_permute_kernel(
         }
     }
     if (tid == 0) offsets[E] = R;
-    if (blocks != nullptr) {   // Algorithm 1, as in emit_block_schedule
+    if (blocks != nullptr) {   // Algorithm 1 and its heavy-first partition, as in emit_block_schedule
         const int nblk = total_blocks;
         if (tid == 0) *num_blocks = nblk;
         for (int q = tid; q < nblk; q += kFusedThreads) {
-            int lo = 0, hi = kMaxExperts - 1;
-            while (lo < hi) {
-                const int mid = (lo + hi + 1) >> 1;
-                if (first[mid] <= q) lo = mid; else hi = mid - 1;
+            const int e = owner_of_block(first, kMaxExperts, q);
+            blocks[2 * q] = e;
+            blocks[2 * q + 1] = (q - first[e]) * M;
+        }
+        if (blocks_mix != nullptr) {
+            const int n1 = total_heavy;
+            if (tid == 0) *num_heavy = n1;
+            for (int q = tid; q < nblk; q += kFusedThreads) {
+                int e, b;
+                if (q < n1) {
+                    e = owner_of_block(firsth, kMaxExperts, q);
+                    b = q - firsth[e];
+                } else {
+                    e = owner_of_block(firstl, kMaxExperts, q - n1);
+                    b = q - n1 - firstl[e];
+                }
+                blocks_mix[2 * q] = e;
+                blocks_mix[2 * q + 1] = b * M;
             }
-            blocks[2 * q] = lo;
-            blocks[2 * q + 1] = (q - first[lo]) * M;
         }
     }
     __syncthreads();
@@ -329,17 +391,18 @@ hipError_t permute_static_scratch(int32_t** ptr) {
 
 hipError_t launch_permute_index(const moe_config& c, const int32_t* topk_idx, int32_t* counts,
                                 int32_t* offsets, int32_t* row_of, int32_t* src_of, int32_t* scratch,
-                                int32_t M, int32_t* blocks, int32_t* num_blocks, hipStream_t s) {
+                                int32_t M, int32_t* blocks, int32_t* num_blocks, int32_t* blocks_mix, int32_t* num_heavy,
+                                hipStream_t s) {
     const int R = c.T * c.k;
     if (R <= kFusedMaxSlots) {
         hipLaunchKernelGGL(fused_permute_kernel, dim3(1), dim3(kFusedThreads), 0, s, topk_idx, R, c.E, counts,
-                           offsets, row_of, src_of, M > 0 ? M : 1, blocks, num_blocks);
+                           offsets, row_of, src_of, M > 0 ? M : 1, blocks, num_blocks, blocks_mix, num_heavy);
         return hipGetLastError();
     }
     const int nchunks = permute_chunks(c);
     hipLaunchKernelGGL(hist_kernel, dim3(nchunks), dim3(kThreads), 0, s, topk_idx, R, c.E, scratch);
     hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(kThreads), 0, s, scratch, nchunks, c.E, R, counts, offsets, M,
-                       blocks, num_blocks);
+                       blocks, num_blocks, blocks_mix, num_heavy);
     hipLaunchKernelGGL(rank_kernel, dim3(nchunks), dim3(kThreads), 0, s, topk_idx, R, c.E, scratch, row_of,
                        src_of);
     return hipGetLastError();
@@ -352,8 +415,9 @@ hipError_t launch_gather_rows(const moe_config& c, const uint16_t* x, const int3
 }
 
 hipError_t launch_block_schedule(const moe_config& c, const int32_t* offsets, int32_t M, int32_t* blocks,
-                                 int32_t* num_blocks, hipStream_t s) {
-    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kThreads), 0, s, offsets, c.E, M, blocks, num_blocks);
+                                 int32_t* num_blocks, int32_t* blocks_mix, int32_t* num_heavy, hipStream_t s) {
+    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kThreads), 0, s, offsets, c.E, M, blocks, num_blocks,
+                       blocks_mix, num_heavy);
     return hipGetLastError();
 }
 

@@ -259,10 +259,16 @@ def test_row_tiles_of_an_expert_side_by_side(G, knobs):
 #   skewed16   : 16 experts under skew 2: one of 4 full tiles + a short one, one of three tiles,
 #                one of two, the rest single blocks or empty, in one launch.  down: single-use
 #                weights, one contiguous eighth of the work per XCD.
+#   mixed8, mixed12 : three multi-tile experts (8, 5 and 2-3 tiles) and five / nine single-block
+#                ones with many rows per expert on average, which is where the down projection
+#                deals its heavy and light blocks evenly over the launch: block by block with
+#                d/256 = 7 feature tiles (mixed8), in units of 8 workgroups with 8 (mixed12).
 _TILE_SHAPES = {
     "five_tiles": (mi.MoEShape("five_tiles", 1100, 2048, 1024, 2, 2, mi.GATE_SOFTMAX), 11, 0.0),
     "nine_tiles": (mi.MoEShape("nine_tiles", 2100, 2048, 1024, 2, 2, mi.GATE_SOFTMAX_RENORM), 12, 0.0),
     "skewed16": (mi.MoEShape("skewed16", 1090, 2048, 1024, 16, 2, mi.GATE_SOFTMAX), 11, 2.0),
+    "mixed8": (mi.MoEShape("mixed8", 2000, 1792, 1024, 8, 2, mi.GATE_SOFTMAX), 11, 2.0),
+    "mixed12": (mi.MoEShape("mixed12", 2000, 2048, 1024, 12, 2, mi.GATE_SOFTMAX), 12, 2.0),
 }
 
 
@@ -278,14 +284,25 @@ def test_multi_tile_experts_all_rows(G, knobs, name):
     layer = G.Layer(s, seed=seed, skew=skew)
     ref = _oracle_full(layer)
     hot = int(ref["counts"].max())
-    assert hot > 4 * 256 and 0 < hot % 256 <= 96, "the fullest expert must end in a short tile"
+    assert hot > 4 * 256 and (name.startswith("mixed") or 0 < hot % 256 <= 96), "the fullest expert must end in a short tile"
     cfg = layer.cfg()
     if name == "five_tiles":
         assert moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<2, false, true, false")
     if name == "skewed16":
         assert moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<1, false, true, true")
         assert sorted(ref["counts"])[-2] > 512 and sorted(ref["counts"])[-3] > 256
+    if name.startswith("mixed"):
+        assert moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<2, false, true, false")
+        assert (ref["counts"] > 256).sum() == 3 and ((ref["counts"] > 0) & (ref["counts"] <= 256)).sum() >= 5
     _say(f"{name}: default launch order, all rows")
+    out = G.run_forward(layer)
+    _all_rows_against_oracle(G, layer, ref, out)
+    # Which workgroup computes a row does not change the row's result as long as k is walked in
+    # the same order.  By default a short last tile of a multi-tile expert walks k rotated (it
+    # streams its panel like a single-block expert); for the bit-for-bit comparisons below that
+    # is switched off, so that a row gives the same bits whichever tile it falls into.
+    knobs(B.KNOB_SHORT_NT, 0)
+    _say(f"{name}: short tiles in step with their siblings, all rows")
     out = G.run_forward(layer)
     _all_rows_against_oracle(G, layer, ref, out)
     for which, value, label in [(B.KNOB_SIDE_BY_SIDE, 0, "tile-major order"), (B.KNOB_EVEN_ROWS, 0, "Algorithm 1's row ranges"),
@@ -299,11 +316,13 @@ def test_multi_tile_experts_all_rows(G, knobs, name):
     # The per-XCD chunking changes which workgroup id computes a block, and single-block experts
     # start their k loop at a step that depends on the id: another order of the same sum, so
     # these two are compared with the oracle, not bit for bit.
-    for value, label in [(0, "no per-XCD chunks"), (1, "per-XCD chunks on both projections")]:
-        knobs(B.KNOB_XCD_CHUNK, value)
+    # The same holds for the dealing of heavy and light blocks over the down projection's launch.
+    for which, value, label in [(B.KNOB_XCD_CHUNK, 0, "no per-XCD chunks"), (B.KNOB_XCD_CHUNK, 1, "per-XCD chunks on both projections"),
+                                (B.KNOB_INTERLEAVE, 0, "down projection in expert order")]:
+        knobs(which, value)
         _say(f"{name}: {label}")
         other = G.run_forward(layer)
-        knobs(B.KNOB_XCD_CHUNK, -1)
+        knobs(which, -1)
         _all_rows_against_oracle(G, layer, ref, other)
 
 
