@@ -2,8 +2,10 @@
 """Benchmark: one MoE layer forward (route -> permute -> gate+up -> down -> combine) on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mixtral] [--T 512]
+    python bench.py --grid "mixtral:1,16,64,256,512,4096:0;qwen2moe:512,4096:0,1,1.5,2" [--steps K]
 
-Prints ONE JSON line.  `value` is tokens/s of the whole layer with all inputs resident in HBM.
+Prints ONE JSON line (or, with --grid, one table row per (shape, T, skew) cell, all cells of a
+shape sharing one set of generated weights: that is how the sweeps under profiles/ are made).  `value` is tokens/s of the whole layer with all inputs resident in HBM.
 `roofline` is for the dominant kernel (the fused gate+up grouped GEMM), timed inside the timed
 region with HIP events recorded by the library on the launch stream.  `cpu_baseline` is the
 fp64 numpy oracle timed on this machine's host cores on a bounded token sample.
@@ -46,6 +48,9 @@ def parse_args():
                     help="feed the GEMMs the row-major [E,N,K] weights instead of the one-time packed copy")
     ap.add_argument("--fuse-combine", action="store_true",
                     help="set MOE_FLAG_FUSE_COMBINE: the weighted combine runs inside the down projection")
+    ap.add_argument("--grid", default="",
+                    help="sweep instead of one point: 'shape:T,T,...:skew,skew,...;shape:...' with shape a preset or "
+                         "d,F,E,k written as custom_d_F_E_k; prints a table, one row per cell")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (torch) so that a rocprofv3 --pmc run of this "
                          "command holds a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -72,6 +77,80 @@ def cpu_baseline(shape, x_cpu, wr_cpu, bias_cpu, seed, sample):
                       f"{len(tokens)} seeded tokens ({dt:.1f} s, includes regenerating and decoding the experts hit)"}, out
 
 
+def grid(args):
+    """Per-stage timings over a grid of cells in one process (the weights of a shape are generated once)."""
+    import paper_2605_23911_amd as moe
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    flags = moe.FLAG_FUSE_COMBINE if args.fuse_combine else 0
+
+    def ev():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(stream)
+        return e
+
+    print(f"{'shape':22s} {'T':>5s} {'skew':>4s} {'act':>4s} {'ms/fwd':>8s} {'tokens/s':>10s} | {'route':>6s} {'perm':>6s} "
+          f"{'gate_up':>8s} {'down':>8s} {'comb':>6s} (us) | gate+up: vs HBM, vs MFMA | down: vs HBM, vs MFMA | "
+          f"layer: vs HBM, vs MFMA", flush=True)
+    for part in args.grid.split(";"):
+        name, Ts, skews = part.split(":")
+        if name.startswith("custom_"):
+            d_, F_, E_, k_ = (int(v) for v in name.split("_")[1:])
+            base = mi.MoEShape(name, 512, d_, F_, E_, k_)
+        else:
+            base = mi.PRESETS[name]
+        wg = torch.empty((base.E, base.F, base.d), dtype=torch.bfloat16, device=dev)
+        wu = torch.empty_like(wg)
+        wd = torch.empty((base.E, base.d, base.F), dtype=torch.bfloat16, device=dev)
+        mi.make_all_experts(base, args.seed, out=(wg, wu, wd))
+        cfg0 = moe.MoEConfig.of(1, base.d, base.F, base.E, base.k, base.gating)
+        pk = None
+        if not args.row_major:
+            pk = torch.empty(moe.packed_weights_size(cfg0), dtype=torch.uint8, device=dev)
+            moe.moe_pack_weights(cfg0, wg, wu, wd, pk)
+            torch.cuda.synchronize()
+            wg = wu = wd = None
+        for T in (int(v) for v in Ts.split(",")):
+            s = base.with_T(T)
+            x, wr = mi.make_x(s, args.seed).to(dev), mi.make_router(s, args.seed).to(dev)
+            for skew in (float(v) for v in skews.split(",")):
+                b = mi.skew_bias(s, skew, args.seed)
+                bias = None if b is None else b.to(dev)
+                cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating, args.tile_m, flags)
+                lay = moe.forward_workspace_layout(cfg)
+                ws = torch.zeros(lay.total, dtype=torch.uint8, device=dev)
+                y = torch.empty((s.T, s.d), dtype=torch.bfloat16, device=dev)
+                for _ in range(args.warmup):
+                    moe.moe_forward(cfg, x, wr, bias, wg, wu, wd, y, ws, W_packed=pk)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(args.steps):
+                    moe.moe_forward(cfg, x, wr, bias, wg, wu, wd, y, ws, W_packed=pk)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) * 1e3 / args.steps
+                evs = [[ev() for _ in range(6)] for _ in range(args.steps)]
+                torch.cuda.synchronize()
+                for row in evs:
+                    moe.moe_forward_staged(cfg, x, wr, bias, wg, wu, wd, y, ws, [e.cuda_event for e in row], W_packed=pk)
+                torch.cuda.synchronize()
+                st = [float(np.median([row[i].elapsed_time(row[i + 1]) for row in evs])) * 1e3 for i in range(5)]
+                counts = ws[lay.counts: lay.counts + 4 * s.E].view(torch.int32).cpu().numpy()
+                ea, R = int((counts > 0).sum()), s.R
+                gub, guf = 4 * s.d * s.F * ea + 2 * R * s.d + 2 * R * s.F, 4 * R * s.d * s.F
+                dnb, dnf = 2 * s.d * s.F * ea + 2 * R * s.d + 2 * R * s.F, 2 * R * s.d * s.F
+                lb = (6 * s.d * s.F * ea + 2 * s.E * s.d + 2 * s.T * s.d + 2 * R * s.d + 4 * R * s.F + 4 * R * s.d
+                      + 2 * s.T * s.d + 16 * R)
+                lf = s.T * (6 * s.k * s.d * s.F + 2 * s.E * s.d)
+                hb = lambda nbytes, us: nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
+                mf = lambda flops, us: flops / (us * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS
+                print(f"{name:22s} {T:5d} {skew:4.1f} {ea:4d} {ms:8.4f} {s.T / (ms * 1e-3):10.0f} | {st[0]:6.1f} {st[1]:6.1f} "
+                      f"{st[2]:8.1f} {st[3]:8.1f} {st[4]:6.1f}      |     {hb(gub, st[2]):.3f}  {mf(guf, st[2]):.3f}      |   "
+                      f"{hb(dnb, st[3]):.3f}  {mf(dnf, st[3]):.3f}    |    {hb(lb, ms * 1e3):.3f}  {mf(lf, ms * 1e3):.3f}", flush=True)
+                del ws, y
+        del pk, wg, wu, wd
+        torch.cuda.empty_cache()
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -86,6 +165,8 @@ def main():
 
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.grid:
+        return grid(args)
     if args.shape:
         d_, F_, E_, k_ = (int(v) for v in args.shape.split(","))
         s = mi.MoEShape(f"d{d_}-F{F_}-E{E_}-k{k_}", args.T, d_, F_, E_, k_)
@@ -174,11 +255,15 @@ def main():
         roofline = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": ach / HBM_PEAK_GBS, "traffic": None}
     kname = moe.ffn_kernel_name(cfg, 0, packed is not None)
-    try:    # HBM bytes per launch measured with rocprofv3 --pmc for this workload and kernel, if recorded
+    # HBM bytes per launch from rocprofv3 --pmc counters: they cannot be read from inside this process, so the figure
+    # of the committed counter run (profiles/mixtral_T512_hbm_traffic.txt) is reported, and only for the workload and
+    # the kernel instance it was taken on: any other point, or a renamed kernel, reports null rather than a stale number.
+    try:
         rec = json.load(open(os.path.join(ROOT, "profiles", "traffic.json"))).get(
             f"{s.name} T={s.T} {'packed' if packed is not None else 'row-major'}")
-        if rec and rec["kernel"] == kname and args.skew == 0.0 and args.tile_m == 0:
+        if rec and rec["kernel"] == kname and args.skew == 0.0 and args.tile_m == 0 and not args.fuse_combine:
             roofline["traffic"] = rec["traffic_bytes"]
+            roofline["traffic_source"] = rec.get("source", "profiles/traffic.json")
     except (OSError, ValueError, KeyError):
         pass
     roofline.update({"kernel": kname, "kernel_ms": gate_up_ms,
