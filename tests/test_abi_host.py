@@ -80,6 +80,15 @@ def test_null_alignment_and_workspace_errors_need_no_gpu(L):
     assert L.moe_forward(C.byref(c), p, p, None, p, p, p, None, p + 8, p, 1 << 30, None) == -3
     assert L.moe_forward(C.byref(c), p, p, None, None, None, None, None, p, p, 1 << 30, None) == -1
     assert L.moe_block_schedule(C.byref(c), p, 0, p, p, None) == -2
+    assert L.moe_block_schedule(C.byref(c), p, (1 << 30) + 1, p, p, None) == -2
+    assert moe.max_blocks(c, (1 << 30) + 1) == 0
+    # the entry point without a workspace argument: same checks, plus the size of its device array
+    assert L.moe_permute_static(C.byref(c), p, None, p, p, p, p, p, None) == -1
+    assert L.moe_permute_static(C.byref(c), p, p, p, p, p, p, None, None) == -1
+    assert L.moe_permute_static(C.byref(c), p + 4, p, p, p, p, p, p, None) == -3
+    big = moe.MoEConfig.of(40000, 128, 64, 256, 8)      # 313 chunks x 256 experts > 65536 int32
+    assert L.moe_permute_static(C.byref(big), p, p, p, p, p, p, p, None) == -5
+    assert L.moe_permute_static(C.byref(moe.MoEConfig.of(0, 256, 512, 8, 2)), p, p, p, p, p, p, p, None) == 0
     # T == 0 is a no-op that succeeds without a device
     z = moe.MoEConfig.of(0, 256, 512, 8, 2)
     assert L.moe_forward(C.byref(z), p, p, None, p, p, p, None, p, p, 1 << 20, None) == 0
