@@ -790,7 +790,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
     Tile t;
     int tile, nt;
-    bool halves = false, chunked = false;
+    bool halves = false, chunked = false, dealt = false;
     const int total = *a.num_blocks * a.n_tiles_n;
     {
         int w = blockIdx.x, sub = 0;
@@ -841,6 +841,7 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
                 const long long before = (long long)p * hu / tu, upto = (long long)(p + 1) * hu / tu;
                 const int unit = upto > before ? (int)before : hu + (p - (int)before);
                 w = unit * U + r;
+                dealt = U != 8;   // whole units of 8 ids keep an expert's workgroups on the XCDs the order below assumes
             }
         }
         tile = w / a.n_tiles_n;
@@ -848,15 +849,18 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
         if (halves) nt = 2 * nt + sub;   // index of the 128-feature tile the IB = 1 body works on
     }
     // Row tiles of one expert side by side.  The workgroups of an expert with n row tiles are a
-    // contiguous span of n * n_tiles_n ids that starts at a multiple of 8, so id % 8 (the XCD the
-    // hardware deals the workgroup to) is a property of the position in the span.  In plain
-    // tile-major order the n workgroups that read the same weight panel are n_tiles_n ids apart:
-    // they start microseconds apart, and an XCD's 4 MiB of L2 hold only about three k steps of
-    // its 32 workgroups' streams, so each of them fetches the panel from beyond L2 for itself.
-    // Inside the span the order is therefore (feature tile, row tile) per XCD: the n row tiles of
-    // a panel are consecutive workgroups of one XCD, start together and walk k in step.  A short
-    // last tile (a different, faster body) would not stay in step anyway: those go to the end of
-    // the span.  The XCD of every (expert, feature tile) pair is the same as in tile-major order.
+    // contiguous span of n * n_tiles_n launch positions; the hardware deals workgroup id to XCD
+    // id % 8, so the positions of the span that are 8 apart (one "class", position % 8) run on one
+    // XCD, one after the other.  In plain tile-major order the n workgroups that read the same
+    // weight panel are n_tiles_n positions apart: they start microseconds apart, on whatever XCD
+    // that distance leads to, and an XCD's 4 MiB of L2 hold only about three k steps of its 32
+    // workgroups' streams, so each of them fetches the panel from beyond L2 for itself.  Inside
+    // the span the order is therefore (feature tile, row tile) per class: the n row tiles of a
+    // panel are consecutive positions of one class, i.e. consecutive workgroups of one XCD, start
+    // together and walk k in step.  A class of c positions holds c / n whole panels; the c % n
+    // positions left over in each class take the remaining panels' tiles in turn (those panels are
+    // spread over several XCDs; none when n_tiles_n is a multiple of 8).  A short last tile (a
+    // different, faster body) would not stay in step anyway: those go to the end of the span.
     // (Mixtral shape, T=4096: layer -3 %; T=8192 -2 %; no effect on single-tile experts.)
     // The schedule entry is read once: the look-ups (block count, entry, expert offsets, for
     // the gate+up projection the source row) are dependent loads in front of the block's first
@@ -871,22 +875,35 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     int ti = r_in / bm;                                // which of them this workgroup is
     // see below; a.even: 0 never, 1 experts of up to three row tiles, 2 those while the launch is at most two rounds, 3 always
     const bool even = a.even == 3 || (n <= 3 && (a.even == 1 || (a.even == 2 && total <= 2 * a.slots)));
-    if (a.sib && !halves && !chunked && (a.n_tiles_n & 7) == 0 && n >= 2) {
+    if (a.sib && !halves && !chunked && !dealt && n >= 2) {
         auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 7 ? 8 : c; };
-        const int nt8 = a.n_tiles_n >> 3;
-        const int l = ti * a.n_tiles_n + nt;           // index inside the expert's span of workgroups
-        const int x = l & 7, m = l >> 3;               // the span starts at a multiple of 8: x is the XCD
         // tiles that run the same body as the first one (all of them when the rows are dealt evenly)
         const int nf = (even || body(n_e - (n - 1) * bm) == body(bm)) ? n : n - 1;
-        int ntl;
-        if (m < nf * nt8) {
-            ntl = m / nf;
-            ti = m - ntl * nf;
-        } else {
+        const int l = ti * a.n_tiles_n + nt;           // position inside the expert's span
+        const int span = nf * a.n_tiles_n;             // positions of the tiles that keep pace with each other
+        if (l >= span) {
             ti = n - 1;
-            ntl = m - nf * nt8;
+            nt = l - span;
+        } else {
+            const int cls = l & 7, j = l >> 3;         // class of the position, index inside the class
+            int left_before = 0, whole = 0, mine = 0;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int positions = (span - c + 7) >> 3, panels = positions / nf;   // non-increasing in c
+                if (c < cls) left_before += positions - panels * nf;
+                if (c == cls) mine = panels;
+                whole += panels;
+            }
+            if (j < mine * nf) {
+                // the p-th whole panel of every class: panels p * 8 + class (at any time the XCDs work on neighbouring panels)
+                nt = (j / nf) * 8 + cls;
+                ti = j % nf;
+            } else {
+                const int m = left_before + (j - mine * nf);
+                nt = whole + m / nf;
+                ti = m % nf;
+            }
         }
-        nt = ntl * 8 + x;
     }
     // Rows of a multi-tile expert dealt evenly over its n schedule entries, in whole 32-row blocks:
     // Algorithm 1 gives 1040 rows as 4 x 256 + 16, and the 16-row tile streams a whole weight

@@ -269,6 +269,9 @@ _TILE_SHAPES = {
     "skewed16": (mi.MoEShape("skewed16", 1090, 2048, 1024, 16, 2, mi.GATE_SOFTMAX), 11, 2.0),
     "mixed8": (mi.MoEShape("mixed8", 2000, 1792, 1024, 8, 2, mi.GATE_SOFTMAX), 11, 2.0),
     "mixed12": (mi.MoEShape("mixed12", 2000, 2048, 1024, 12, 2, mi.GATE_SOFTMAX), 12, 2.0),
+    # feature-tile counts that are no multiples of 8 (10 for gate+up, 6 for the down projection): the
+    # side-by-side order then leaves some panels' row tiles spread over several XCDs
+    "odd_tiles": (mi.MoEShape("odd_tiles", 1600, 1536, 1280, 3, 2, mi.GATE_SOFTMAX), 11, 0.0),
 }
 
 
