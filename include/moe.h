@@ -96,8 +96,9 @@ const char* moe_status_string(moe_status s);
 
 /* Tile height (Alg. 1's M) the library uses for this config: cfg->tile_m if non-zero
  * (must be 32, 64, 96, 128, 160, 192 or 256), else 256 (the GEMM kernels adapt to the rows each
- * block really holds), or 32 when there are so few rows in all that the down projection is
- * run by the K-split kernel.
+ * block really holds), 128 for many experts of a few rows each at up to 128 tokens (kernels built
+ * for two workgroups per CU), or 32 when there are so few rows in all that the down projection
+ * is run by the K-split kernel.
  * Returns 0 for an invalid config. */
 int32_t moe_tile_m(const moe_config* cfg);
 

@@ -96,6 +96,7 @@ int32_t moe_tile_m(const moe_config* c) {
     const long long R = (long long)c->T * c->k;
     const long long active = c->E < R ? c->E : R;
     if ((long long)(c->d / 128) * active < 256 && R <= 32) return 32;
+    if (two_workgroups_per_cu(*c)) return 128;   // see moe_internal.hpp
     return 256;
 }
 

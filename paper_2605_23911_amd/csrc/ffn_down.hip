@@ -15,6 +15,7 @@ const Variant kDown[] = {
     /*5*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true>"},
     /*6*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true>"},
     /*7*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false>"},
+    /*8*/ {128, true, launch_tile_mixed<1, false, true, true, true>, "tile_kernel_mixed<1, false, true, true, true>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);
 
@@ -32,6 +33,7 @@ int pick(int M, bool packed, const moe_config& c) {
     if (few_rows && M <= 32) return packed ? 3 : 1;
     if (few_rows && M <= 64) return packed ? 4 : 2;
     if (!packed) return 0;   // row-major lines are consumed by four loads each: cached loads only
+    if (M <= 128 && two_workgroups_per_cu(c)) return 8;
     // Per-block regime selection (tile_kernel_mixed).  Non-temporal weight loads for single-block
     // experts while the token buffers are small; with many rows per expert on average, the
     // two-weight-block form with cached loads throughout.

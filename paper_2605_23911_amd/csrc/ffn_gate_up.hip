@@ -7,22 +7,23 @@ namespace {
 
 // {tallest block, packed?, launcher, kernel template instance as rocprofv3 prints it}.
 // tile_kernel<IB, gateup, STAGES, XD, packed, NT weights>,
-// tile_kernel_mixed<IB, gateup, packed, NT weights for single-block experts>.
+// tile_kernel_mixed<IB, gateup, packed, NT weights for single-block experts, two workgroups per CU>.
 const Variant kGateUp[] = {
     /*0*/ {256, false, launch_tile<1, true, 2, 1, false, false>, "tile_kernel<1, true, 2, 1, false, false>"},
     /*1*/ {256, true, launch_tile_mixed<1, true, true, true>, "tile_kernel_mixed<1, true, true, true>"},
+    /*2*/ {128, true, launch_tile_mixed<1, true, true, true, true>, "tile_kernel_mixed<1, true, true, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
 
-// Packed weights: one kernel for every schedule and every routing distribution.  It picks the
+// Packed weights: one kernel for every schedule and every routing distribution (built a second
+// time for two workgroups per CU, see two_workgroups_per_cu).  It picks the
 // body per block from the rows the block holds and the regime per block from the rows its expert
 // holds (tile_kernel_mixed).  Row-major weights: the register-staged kernel with cached loads
 // (a row-major 128-byte line is consumed by four load instructions of a lane pair, so the
 // non-temporal hint would drop it between them: measured 1.7x slower).
 int pick(int M, bool packed, const moe_config& c) {
-    (void)M;
-    (void)c;
-    return packed ? 1 : 0;
+    if (!packed) return 0;
+    return (M <= 128 && two_workgroups_per_cu(c)) ? 2 : 1;
 }
 
 }  // namespace

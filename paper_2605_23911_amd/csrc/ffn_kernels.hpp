@@ -750,10 +750,18 @@ __global__ __launch_bounds__(kThreads) void tile_kernel(const GemmArgs a) {
 }
 
 // The dynamic-height kernel with the LDS-DMA token tile.  LDS: (XD+1) buffers of up to 32 KiB.
-template <int IB, bool GATEUP, bool PACKED, bool WNT = false>
+template <int IB, bool GATEUP, bool PACKED, bool WNT = false, bool HALF = false>
 __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, int nt, uint16_t* xs) {
     constexpr int NI = IB * (GATEUP ? 2 : 1);
     constexpr int SD = NI >= 4 ? 3 : 4;
+    if constexpr (HALF) {   // blocks of at most 128 rows, two workgroups per CU: register budget 256 per wavefront
+        switch ((t.rows + 31) / 32) {
+            case 1: return tile_body_dma<8, 1, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
+            case 2: return tile_body_dma<8, 2, IB, GATEUP, 3, 3, PACKED, WNT>(a, t, nt, xs);
+            case 3: return tile_body_dma<8, 3, IB, GATEUP, 2, 3, PACKED, WNT>(a, t, nt, xs);
+            default: return tile_body_dma<8, 4, IB, GATEUP, 2, 3, PACKED, WNT>(a, t, nt, xs);
+        }
+    }
     switch ((t.rows + 31) / 32) {
         case 1: return tile_body_dma<8, 1, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
         case 2: return tile_body_dma<8, 2, IB, GATEUP, SD, 3, PACKED, WNT>(a, t, nt, xs);
@@ -785,8 +793,8 @@ __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, i
 // round precedes it: with many rounds the workgroups do not end together, there is no common
 // "last round" to shorten, and the less efficient halves cost more than they gain (measured:
 // -10 % at T=2048, +3..5 % at T=4096 and T=8192 without this condition).
-template <int IB, bool GATEUP, bool PACKED, bool WNT>
-__global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) {
+template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
+__global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(const GemmArgs a) {
     extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
     Tile t;
     int tile, nt;
@@ -942,12 +950,12 @@ __global__ __launch_bounds__(kThreads) void tile_kernel_mixed(const GemmArgs a) 
     const bool shared = multi || a.no_nt;
     if constexpr (IB == 2 && !GATEUP) {
         if (halves) {
-            if (shared) return dma_dispatch<1, GATEUP, PACKED>(b, t, nt, xs);
-            return dma_dispatch<1, GATEUP, PACKED, WNT>(b, t, nt, xs);
+            if (shared) return dma_dispatch<1, GATEUP, PACKED, false, HALF>(b, t, nt, xs);
+            return dma_dispatch<1, GATEUP, PACKED, WNT, HALF>(b, t, nt, xs);
         }
     }
-    if (shared) return dma_dispatch<IB, GATEUP, PACKED>(b, t, nt, xs);
-    dma_dispatch<IB, GATEUP, PACKED, WNT>(b, t, nt, xs);
+    if (shared) return dma_dispatch<IB, GATEUP, PACKED, false, HALF>(b, t, nt, xs);
+    dma_dispatch<IB, GATEUP, PACKED, WNT, HALF>(b, t, nt, xs);
 }
 
 // =============================================================================================
@@ -1093,11 +1101,11 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int IB, bool GATEUP, bool PACKED, bool WNT>
+template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
 hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     constexpr int BN = 4 * IB * 32;
-    constexpr int lds = 4 * 8 * 32 * 128;   // the DMA ring: XD+1 = 4 buffers of 256 rows x 128 bytes
-    auto kern = tile_kernel_mixed<IB, GATEUP, PACKED, WNT>;
+    constexpr int lds = 4 * (HALF ? 4 : 8) * 32 * 128;   // the DMA ring: XD+1 = 4 buffers of 256 (128) rows x 128 bytes
+    auto kern = tile_kernel_mixed<IB, GATEUP, PACKED, WNT, HALF>;
     // once per process and kernel: not allowed while a stream is being captured into a graph
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds);

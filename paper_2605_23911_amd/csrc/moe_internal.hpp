@@ -119,6 +119,23 @@ hipError_t launch_pack(const moe_config& c, const uint16_t* wg, const uint16_t* 
 hipError_t launch_combine(const moe_config& c, const uint16_t* y_perm, const int32_t* row_of,
                           const float* topk_w, uint16_t* y, hipStream_t s);
 
+// Many experts with a few rows each (Qwen2-MoE and DeepSeek-V3 shapes at up to 128 tokens): a
+// projection is thousands of short workgroups that stream a weight panel each, and what a CU
+// loses between two of them (schedule look-up, first loads, epilogue, launch of the next: ~5 us
+// of ~45) shows as 10 % of the down projection.  The schedule then uses blocks of at most 128
+// rows and the GEMM kernels are the builds for two workgroups per CU (half the LDS ring, at most
+// 256 registers), so that one workgroup streams while its neighbour starts or ends.
+// Only up to 128 tokens: no expert can then hold more than one such block, whatever the routing
+// (with heavier experts under routing skew the shorter blocks and their shallower pipelines cost
+// more than the overlap gains: DeepSeek-V3 shape, 512 tokens, skew 1.5: +10 %).  Only for
+// launches of at least four rounds: the hardware fills a CU with two workgroups before it moves
+// on, so a launch of 256 would use half the chip.
+inline bool two_workgroups_per_cu(const moe_config& c) {
+    const long long R = (long long)c.T * c.k;
+    const long long active = c.E < R ? c.E : R;
+    return c.T <= 128 && R <= 32ll * c.E && (long long)(c.d / 128) * active >= 1024;
+}
+
 inline int permute_chunks(const moe_config& c) {
     long long R = (long long)c.T * c.k;
     return (int)((R + kPermChunk - 1) / kPermChunk);

@@ -397,6 +397,44 @@ def test_down_projection_variants_and_graph_replay(G, knobs):
             assert torch.equal(y, y_eager)
 
 
+@pytest.mark.parametrize("skew", [0.0, 2.0])
+def test_two_workgroups_per_cu(G, knobs, skew):
+    """Many experts with few rows each at up to 128 tokens: blocks of at most 128 rows and the GEMM
+    kernels built for two workgroups per CU.  Chosen by the rule on a 256-expert shape (uniform
+    routing: 3 rows per expert; skewed: one expert holds most tokens, the four-block body), and
+    forced onto the ragged shape; every element against the oracle, bit-equal with the combine
+    folded in."""
+    import paper_2605_23911_amd as moe
+    import paper_2605_23911_amd.binding as B
+    s = mi.MoEShape("many_small", 100, 1024, 256, 256, 8, mi.GATE_SOFTMAX)
+    layer = G.Layer(s, seed=9, skew=skew)
+    cfg = layer.cfg()
+    assert moe.tile_m(cfg) == 128
+    assert moe.ffn_kernel_name(cfg, 0, True) == "tile_kernel_mixed<1, true, true, true, true>"
+    assert moe.ffn_kernel_name(cfg, 1, True) == "tile_kernel_mixed<1, false, true, true, true>"
+    beyond = moe.MoEConfig.of(129, s.d, s.F, s.E, s.k, s.gating)     # 129 tokens: the one-workgroup-per-CU kernels
+    assert moe.tile_m(beyond) == 256 and "true, true, true>" not in moe.ffn_kernel_name(beyond, 1, True)
+    ref = _oracle_full(layer)
+    if skew > 0:
+        assert ref["counts"].max() > 64
+    _say(f"two workgroups per CU by rule, skew {skew}: all rows")
+    out = G.run_forward(layer)
+    _all_rows_against_oracle(G, layer, ref, out)
+    fused = G.run_forward(layer, flags=moe.FLAG_FUSE_COMBINE)
+    for key in ("h", "y_perm", "y"):
+        assert np.array_equal(out[key], fused[key]), key
+    # forced: ragged shape, blocks of 128 rows (experts of up to ~300 rows: several blocks each)
+    r = mi.MoEShape("ragged", 333, 192, 320, 7, 3, mi.GATE_SOFTMAX_RENORM)
+    rl = G.Layer(r, seed=3, skew=skew)
+    rref = _oracle_full(rl)
+    knobs(B.KNOB_GATE_UP_VARIANT, 2)
+    knobs(B.KNOB_DOWN_VARIANT, 8)
+    assert moe.ffn_kernel_name(rl.cfg(128), 1, True) == "tile_kernel_mixed<1, false, true, true, true>"
+    _say(f"two workgroups per CU forced onto the ragged shape, skew {skew}")
+    out = G.run_forward(rl, tile_m=128)
+    _all_rows_against_oracle(G, rl, rref, out)
+
+
 def test_zero_tokens_is_a_noop(G):
     import paper_2605_23911_amd as moe
     cfg = moe.MoEConfig.of(0, 64, 128, 4, 2)
