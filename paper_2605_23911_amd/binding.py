@@ -157,7 +157,7 @@ def workspace_size(cfg) -> int:
 
 # Test knobs of the library (csrc/moe_internal.hpp); -1 restores the selection rule.
 (KNOB_GATE_UP_VARIANT, KNOB_DOWN_VARIANT, KNOB_SIDE_BY_SIDE, KNOB_EVEN_ROWS, KNOB_XCD_CHUNK, KNOB_ROT, KNOB_SHORT_NT,
- KNOB_FUSE_COMBINE, KNOB_INTERLEAVE) = range(9)
+ KNOB_FUSE_COMBINE, KNOB_INTERLEAVE, KNOB_NO_NT, KNOB_ROUTE_EXACT) = range(11)
 
 
 def test_knob(which: int, value: int) -> int:

@@ -51,6 +51,7 @@ enum {
     kKnobFuseCombine = 7,     // 0: moe_forward always launches the combine kernel, 1: folds it into the down projection whenever the kernel can
     kKnobInterleave = 8,      // 0: launch order = block order (no dealing of heavy and light blocks over the launch)
     kKnobNoNt = 9,            // 1: cached weight loads for single-block experts too
+    kKnobRouteExact = 10,     // 1: every logit in fp64 at any size; 0: bf16 first pass + exact candidates from 256 tokens on
     kNumKnobs = 12
 };
 extern int g_knobs[kNumKnobs];

@@ -174,6 +174,59 @@ def test_router_paths_agree_with_the_oracle(G, T, E):
         assert np.abs(w.astype(np.float64) - w_ref).max() <= 1e-6
 
 
+@pytest.mark.parametrize("T,E,k,d", [(255, 16, 2, 320), (256, 16, 2, 320), (300, 40, 4, 320), (700, 100, 8, 448),
+                                      (512, 256, 8, 1024)])
+def test_router_first_pass_and_exact_candidates(G, knobs, T, E, k, d):
+    """For large batches (here: forced from 256 tokens on) the router computes all logits on the bf16 matrix cores first and
+    recomputes only the experts within the error bound of the k-th largest in fp64: the same
+    indices in the same order as the oracle, weights within 1e-6, on one, two and four 32-expert
+    tiles per wavefront with ragged last tiles, all three gatings; and the same indices as the
+    all-fp64 path (255 tokens take that path by themselves)."""
+    import paper_2605_23911_amd.binding as B
+    for gating in (mi.GATE_SOFTMAX, mi.GATE_SOFTMAX_RENORM, mi.GATE_SIGMOID_NORM):
+        s = mi.MoEShape("route2", T, d, 64, E, k, gating)
+        _say(f"router T={T} E={E} k={k} d={d} gating={gating}")
+        layer = G.Layer(s, seed=31 + gating, skew=1.0)
+        idx_ref, w_ref, gap = orc.route(layer.x_bits, layer.wr_bits, layer.bias_np, s.k, gating)
+        assert gap.min() > GAP_MIN, "seeded logits too close to certify index parity"
+        knobs(B.KNOB_ROUTE_EXACT, 0)     # the first pass from 256 tokens on (by itself: from 2^19 logits on)
+        idx, w = G.run_route(layer)
+        assert np.array_equal(idx, idx_ref)
+        assert np.abs(w.astype(np.float64) - w_ref).max() <= 1e-6
+        knobs(B.KNOB_ROUTE_EXACT, 1)
+        idx2, w2 = G.run_route(layer)
+        knobs(B.KNOB_ROUTE_EXACT, -1)
+        assert np.array_equal(idx2, idx_ref)
+        assert np.abs(w2.astype(np.float64) - w.astype(np.float64)).max() <= 3e-7
+
+
+def test_router_ties_on_the_first_pass_path(G, knobs):
+    """Exact ties, where the first pass cannot tell experts apart: duplicated router rows (the
+    lower index must win, both at the selection boundary and inside the selected set) and an
+    all-zero router (every expert is a candidate: experts 0..k-1, weights 1/E)."""
+    import paper_2605_23911_amd.binding as B
+    knobs(B.KNOB_ROUTE_EXACT, 0)
+    s = mi.MoEShape("ties", 300, 320, 64, 70, 4, mi.GATE_SOFTMAX)
+    layer = G.Layer(s, seed=5)
+    wr = layer.wr_cpu.clone()
+    wr[9] = wr[2]
+    wr[69] = wr[0]
+    wr[33] = wr[34]
+    layer.wr_cpu = wr
+    layer.wr = wr.to(G.DEV)
+    idx_ref, w_ref, _ = orc.route(layer.x_bits, layer.wr_bits, None, s.k, s.gating)
+    idx, w = G.run_route(layer)
+    assert np.array_equal(idx, idx_ref)
+    assert np.abs(w.astype(np.float64) - w_ref).max() <= 1e-6
+    both = ((idx == 2).any(axis=1) & (idx == 9).any(axis=1)).sum(), ((idx == 2).any(axis=1) ^ (idx == 9).any(axis=1)).sum()
+    assert both[0] > 0 and both[1] > 0, "the duplicated pair should appear both inside the top-k and across its boundary"
+    layer.wr_cpu = torch.zeros_like(wr)
+    layer.wr = layer.wr_cpu.to(G.DEV)
+    idx, w = G.run_route(layer)
+    assert np.array_equal(idx, np.tile(np.arange(s.k, dtype=np.int32), (s.T, 1)))
+    assert np.abs(w - 1.0 / s.E).max() <= 1e-7
+
+
 @pytest.mark.parametrize("shape", [("a", 333, 192, 320, 7, 3), ("b", 1500, 256, 384, 4, 2)])
 def test_forward_equals_the_stage_entry_points(G, shape):
     """moe_forward reads token rows through src_of inside the gate+up kernel; moe_permute +
