@@ -12,9 +12,9 @@ const Variant kDown[] = {
     /*2*/ {64, false, launch_skinny<2, false, 4, 4, false>, "skinny_kernel<2, false, 4, 4, false>"},
     /*3*/ {32, true, launch_skinny<1, false, 4, 4, true>, "skinny_kernel<1, false, 4, 4, true>"},
     /*4*/ {64, true, launch_skinny<2, false, 4, 4, true>, "skinny_kernel<2, false, 4, 4, true>"},
-    /*5*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true>"},
-    /*6*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true>"},
-    /*7*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false>"},
+    /*5*/ {256, true, launch_tile_mixed<1, false, true, true>, "tile_kernel_mixed<1, false, true, true, false>"},
+    /*6*/ {256, true, launch_down_mixed_wide_nt, "tile_kernel_mixed<2, false, true, true, false>"},
+    /*7*/ {256, true, launch_down_mixed_wide, "tile_kernel_mixed<2, false, true, false, false>"},
     /*8*/ {128, true, launch_tile_mixed<1, false, true, true, true>, "tile_kernel_mixed<1, false, true, true, true>"},
 };
 constexpr int kNumDown = sizeof(kDown) / sizeof(kDown[0]);

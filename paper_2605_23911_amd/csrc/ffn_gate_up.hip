@@ -10,7 +10,7 @@ namespace {
 // tile_kernel_mixed<IB, gateup, packed, NT weights for single-block experts, two workgroups per CU>.
 const Variant kGateUp[] = {
     /*0*/ {256, false, launch_tile<1, true, 2, 1, false, false>, "tile_kernel<1, true, 2, 1, false, false>"},
-    /*1*/ {256, true, launch_tile_mixed<1, true, true, true>, "tile_kernel_mixed<1, true, true, true>"},
+    /*1*/ {256, true, launch_tile_mixed<1, true, true, true>, "tile_kernel_mixed<1, true, true, true, false>"},
     /*2*/ {128, true, launch_tile_mixed<1, true, true, true, true>, "tile_kernel_mixed<1, true, true, true, true>"},
 };
 constexpr int kNumGateUp = sizeof(kGateUp) / sizeof(kGateUp[0]);
