@@ -87,11 +87,13 @@ hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_
     if (id < 0) id = pick(M, packed, c);
     if (kDown[id].M < M) return hipErrorInvalidValue;
     // The two-weight-block kernel with cached loads (the choice once experts hold many rows, i.e.
-    // whenever routing skew has produced multi-block experts in a large batch) reads the list
-    // that holds the heavy blocks first and deals the two classes evenly over its launch.
+    // whenever routing skew has produced multi-block experts in a large batch) is also given the
+    // list that holds the heavy blocks first: it deals the two classes evenly over its launch when
+    // the light class is a large enough share of it, and keeps Algorithm 1's order otherwise.
     if (id == 7 && blocks_mix != nullptr && num_heavy != nullptr && knob(kKnobInterleave) != 0) {
-        a.blocks = blocks_mix;
+        a.blocks_mix = blocks_mix;
         a.num_heavy = num_heavy;
+        a.deal_always = knob(kKnobInterleave) > 0;
     }
     if (fuse != nullptr) {
         if (id < 5) return hipErrorInvalidValue;   // only the per-block-regime kernels have the fused epilogue

@@ -62,6 +62,8 @@ struct GemmArgs {
     int M;                      // tile height of the block schedule (rows per block <= M)
     int sib;                    // tile_kernel_mixed: launch the row tiles of one expert side by side (see there)
     int chunk;                  // tile_kernel_mixed: one contiguous eighth of the work per XCD (see there)
+    const int32_t* blocks_mix;  // with num_heavy: the same blocks, those of multi-block experts first (the list the dealt order reads)
+    int deal_always;            // tile_kernel_mixed with num_heavy: deal the two classes whatever their proportion (tests)
     int even;                   // tile_kernel_mixed: rows of a multi-tile expert dealt evenly over its schedule entries
     int no_nt;                  // tile_kernel_mixed: cached weight loads for every block (test knob)
     int short_nt;               // tile_kernel_mixed: tiles of at most this many rows stream their weights non-temporally
@@ -799,6 +801,7 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
     Tile t;
     int tile, nt;
     bool halves = false, chunked = false, dealt = false;
+    const int32_t* blist = a.blocks;   // Algorithm 1's order unless the two classes are dealt (below)
     const int total = *a.num_blocks * a.n_tiles_n;
     {
         int w = blockIdx.x, sub = 0;
@@ -840,10 +843,18 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
         // is a multiple of 8 (id % 8, the XCD, and the side-by-side order below are kept), else
         // one block.  Both classes keep their ascending expert order, so the light experts' weights
         // are still read in address order.  Uniform routing has one class only: nothing moves.
+        // Dealing costs the heavy class: row tiles that share a weight panel no longer start
+        // together (a few percent of their time, whatever the light class holds), and what it
+        // gains grows with the light class's share of the launch.  It is therefore done only
+        // when the single-block experts number at least 2/5 of the multi-block experts' blocks
+        // (measured at T=4096: DeepSeek-V3 shape, 173 / 65 / 31 light against ~130 heavy blocks:
+        // -9.6 %, -5.6 %, -1.8 %; Qwen2-MoE shape, 40 / 45 / 32 against ~130: +2.6 %, +2.8 %, +5.5 %).
         if (a.num_heavy != nullptr && !chunked && !split_round) {
             const int U = (a.n_tiles_n & 7) == 0 ? 8 : a.n_tiles_n;
-            const int hu = *a.num_heavy * a.n_tiles_n / U, tu = total / U, lu = tu - hu;
-            if (hu > 0 && lu > 0) {
+            const int hb = *a.num_heavy, lb = *a.num_blocks - hb;
+            const int hu = hb * a.n_tiles_n / U, tu = total / U, lu = tu - hu;
+            if (hu > 0 && lu > 0 && (a.deal_always || 5 * lb >= 2 * hb)) {
+                blist = a.blocks_mix;
                 const int p = w / U, r = w - p * U;
                 // heavy units among positions [0, p): floor(p * hu / tu); position p is heavy iff that count steps at p
                 const long long before = (long long)p * hu / tu, upto = (long long)(p + 1) * hu / tu;
@@ -875,8 +886,8 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
     // weight and tile loads, each worth several hundred nanoseconds of a ~100 us block.
     if (tile >= *a.num_blocks) return;
     const int bm = a.M < 256 ? a.M : 256;              // rows per schedule entry
-    const int e = a.blocks[2 * tile];
-    const int r_in = a.blocks[2 * tile + 1];
+    const int e = blist[2 * tile];
+    const int r_in = blist[2 * tile + 1];
     const int seg0 = a.offsets[e];
     const int n_e = a.offsets[e + 1] - seg0;
     const int n = (n_e + bm - 1) / bm;                 // row tiles (schedule entries) of this expert

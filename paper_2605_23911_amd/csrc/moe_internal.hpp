@@ -49,7 +49,7 @@ enum {
     kKnobRot = 5,             // k-loop rotation between the workgroups of an XCD, in steps
     kKnobShortNt = 6,         // rows up to which a multi-tile expert's last tile streams its weights non-temporally
     kKnobFuseCombine = 7,     // 0: moe_forward always launches the combine kernel, 1: folds it into the down projection whenever the kernel can
-    kKnobInterleave = 8,      // 0: launch order = block order (no dealing of heavy and light blocks over the launch)
+    kKnobInterleave = 8,      // 0: launch order = block order (no dealing of heavy and light blocks over the launch), 1: dealt whatever the classes' proportion
     kKnobNoNt = 9,            // 1: cached weight loads for single-block experts too
     kKnobRouteExact = 10,     // 1: every logit in fp64 at any size; 0: bf16 first pass + exact candidates from 256 tokens on
     kNumKnobs = 12

@@ -374,7 +374,8 @@ def test_multi_tile_experts_all_rows(G, knobs, name):
     # these two are compared with the oracle, not bit for bit.
     # The same holds for the dealing of heavy and light blocks over the down projection's launch.
     for which, value, label in [(B.KNOB_XCD_CHUNK, 0, "no per-XCD chunks"), (B.KNOB_XCD_CHUNK, 1, "per-XCD chunks on both projections"),
-                                (B.KNOB_INTERLEAVE, 0, "down projection in expert order")]:
+                                (B.KNOB_INTERLEAVE, 0, "down projection in expert order"),
+                                (B.KNOB_INTERLEAVE, 1, "heavy and light blocks dealt whatever their proportion")]:
         knobs(which, value)
         _say(f"{name}: {label}")
         other = G.run_forward(layer)
