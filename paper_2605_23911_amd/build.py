@@ -11,6 +11,8 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_NAME = "libmoe_mi355x.so"
 LIB_PATH = os.path.join(PKG_DIR, LIB_NAME)
+PROBE_SRC = "mfma_ceiling_probe.hip"   # stand-alone measurement program, not linked into the library
+PROBE_PATH = os.path.join(PKG_DIR, "mfma_ceiling_probe")
 SOURCES = ["ffn_down_wide.hip", "ffn_gate_up.hip", "ffn_down.hip", "api.hip", "route.hip", "permute.hip", "pack.hip", "combine.hip"]
 
 HIPCC_FLAGS = [
@@ -58,5 +60,13 @@ def build_library(verbose: bool = False, extra_flags=(), jobs: int = 8) -> str:
     return LIB_PATH
 
 
+def build_probe(verbose: bool = False) -> str:
+    """Compile the MFMA-rate measurement program (see its header) into an in-tree executable."""
+    _run([hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          os.path.join(CSRC, PROBE_SRC), "-o", PROBE_PATH], verbose)
+    return PROBE_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe(verbose=True))
