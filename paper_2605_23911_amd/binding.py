@@ -96,6 +96,9 @@ def lib() -> C.CDLL:
                                      C.c_int32]
     L.moe_test_knob.restype = C.c_int32       # test hook, not part of include/moe.h
     L.moe_test_knob.argtypes = [C.c_int32, C.c_int32]
+    L.moe_test_map_launch.restype = C.c_int32  # test hook (host arithmetic only), not part of include/moe.h
+    L.moe_test_map_launch.argtypes = [C.c_int32] * 5 + [i32p, i32p, C.c_int32, i32p, C.c_int32, C.c_int32, C.c_int32,
+                                      C.c_int32, i32p]
     _lib = L
     return L
 
@@ -163,6 +166,32 @@ def workspace_size(cfg) -> int:
 def test_knob(which: int, value: int) -> int:
     """Set a test knob; returns the previous value."""
     return lib().moe_test_knob(which, value)
+
+
+def map_launch(gateup: bool, ib: int, wnt: bool, N: int, M: int, offsets, blocks, blocks_mix=None, num_heavy: int = 0,
+               cus: int = 256, slack_blocks: int = 0):
+    """Test hook: what every workgroup of a per-block-regime GEMM launch would work on, computed on
+    the host by the code the kernels run.  offsets [E+1], blocks / blocks_mix [n, 2]: numpy int32
+    (host).  Returns an int32 array [grid, 6] = (has work, expert, first row, rows, feature tile,
+    tile width in units of 128 features)."""
+    import numpy as np
+    offsets = np.ascontiguousarray(offsets, dtype=np.int32)
+    blocks = np.ascontiguousarray(blocks, dtype=np.int32).reshape(-1, 2)
+    nb = blocks.shape[0]
+    as_p = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    if blocks_mix is not None:
+        blocks_mix = np.ascontiguousarray(blocks_mix, dtype=np.int32).reshape(-1, 2)
+        assert blocks_mix.shape[0] == nb
+    max_blocks = nb + slack_blocks
+    tiles = (N + 128 * ib - 1) // (128 * ib)
+    capacity = (max_blocks * tiles + 7) // 8 * 8 + cus
+    out = np.zeros((capacity, 6), dtype=np.int32)
+    grid = lib().moe_test_map_launch(int(gateup), ib, int(wnt), N, M, as_p(offsets), as_p(blocks), nb,
+                                     as_p(blocks_mix) if blocks_mix is not None else None, num_heavy, cus, max_blocks,
+                                     capacity, as_p(out))
+    if grid < 0:
+        raise MoEError(f"moe_test_map_launch refused (gateup={gateup}, ib={ib})")
+    return out[:grid]
 
 
 def forward_workspace_layout(cfg) -> WorkspaceLayout:

@@ -109,3 +109,48 @@ hipError_t launch_down(const moe_config& c, int32_t M, const uint16_t* h, int32_
 }
 
 }  // namespace moe
+
+// Test hook (exported, not declared in include/moe.h): enumerate on the HOST what every workgroup
+// of a per-block-regime GEMM launch would work on, with the launch-order switches and the grid the
+// launcher itself would use.  All array arguments are host memory.  out[w] = {has work, expert,
+// first row, rows, feature tile, feature-tile width in units of 128}; returns the grid size, or -1
+// if it exceeds `capacity` or (gateup, ib) names no kernel.  blocks_mix may be null (no dealing).
+extern "C" __attribute__((visibility("default"))) int32_t moe_test_map_launch(
+    int32_t gateup, int32_t ib, int32_t wnt, int32_t N, int32_t M, const int32_t* offsets, const int32_t* blocks,
+    int32_t num_blocks, const int32_t* blocks_mix, int32_t num_heavy, int32_t cus, int32_t max_blocks, int32_t capacity,
+    int32_t* out) {
+    using namespace moe;
+    GemmArgs a{};
+    a.N = N;
+    a.M = M;
+    a.offsets = offsets;
+    a.blocks = blocks;
+    a.num_blocks = &num_blocks;
+    if (blocks_mix != nullptr && knob(kKnobInterleave) != 0) {
+        a.blocks_mix = blocks_mix;
+        a.num_heavy = &num_heavy;
+        a.deal_always = knob(kKnobInterleave) > 0;
+    }
+    auto run = [&](auto ibc, auto guc, auto wntc) -> int32_t {
+        constexpr int IB = decltype(ibc)::value;
+        constexpr bool GU = decltype(guc)::value, WNT = decltype(wntc)::value;
+        const long long grid = mixed_launch_shape<IB, GU, WNT>(a, max_blocks, cus);
+        if (grid > capacity) return -1;
+        for (int w = 0; w < (int)grid; ++w) {
+            MixedWork m{};
+            const bool has = mixed_assign<IB, GU>(a, w, m);
+            int32_t* o = out + 6 * (size_t)w;
+            o[0] = has;
+            o[1] = m.e; o[2] = m.row0; o[3] = m.rows; o[4] = m.nt;
+            o[5] = m.halves ? 1 : IB;
+        }
+        return (int32_t)grid;
+    };
+    using std::integral_constant;
+    using T_ = std::true_type;
+    using F_ = std::false_type;
+    if (gateup && ib == 1) return wnt ? run(integral_constant<int, 1>{}, T_{}, T_{}) : run(integral_constant<int, 1>{}, T_{}, F_{});
+    if (!gateup && ib == 1) return wnt ? run(integral_constant<int, 1>{}, F_{}, T_{}) : run(integral_constant<int, 1>{}, F_{}, F_{});
+    if (!gateup && ib == 2) return wnt ? run(integral_constant<int, 2>{}, F_{}, T_{}) : run(integral_constant<int, 2>{}, F_{}, F_{});
+    return -1;
+}

@@ -795,21 +795,31 @@ __device__ __forceinline__ void dma_dispatch(const GemmArgs& a, const Tile& t, i
 // round precedes it: with many rounds the workgroups do not end together, there is no common
 // "last round" to shorten, and the less efficient halves cost more than they gain (measured:
 // -10 % at T=2048, +3..5 % at T=4096 and T=8192 without this condition).
-template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
-__global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(const GemmArgs a) {
-    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
-    Tile t;
+//
+// mixed_assign: what workgroup w of a tile_kernel_mixed launch works on.  Integer arithmetic on the launch
+// arguments and the schedule arrays only, callable on the host as well: the CPU tests enumerate
+// whole launches with it (host copies of the arrays) and check that every (row, feature tile) of
+// every expert is covered exactly once in each launch order.
+struct MixedWork {
+    int e, row0, rows, n_e;   // expert, first expert-contiguous row, rows of this workgroup, rows of the expert
+    int nt;                   // feature tile: of IB * 128 features, or of 128 when `halves`
+    bool halves;              // IB == 2 down projection: one 128-feature half of a tile of the split last round (IB = 1 body)
+};
+template <int IB, bool GATEUP>
+__host__ __device__ inline bool mixed_assign(const GemmArgs& a, const int wg, MixedWork& m) {
     int tile, nt;
     bool halves = false, chunked = false, dealt = false;
     const int32_t* blist = a.blocks;   // Algorithm 1's order unless the two classes are dealt (below)
     const int total = *a.num_blocks * a.n_tiles_n;
+    int split_from = total;            // first position (in two-block tiles) of a split last round
     {
-        int w = blockIdx.x, sub = 0;
+        int w = wg, sub = 0;
         bool split_round = false;
         if constexpr (IB == 2 && !GATEUP) {
             if (a.slots > 0) {
                 const int full = total / a.slots * a.slots, rem = total - full;
                 split_round = rem > 0 && 2 * rem <= a.slots && full <= a.slots;
+                if (split_round) split_from = full;
                 if (split_round && w >= full) {
                     const int h = w - full;
                     w = full + (h >> 1);
@@ -826,11 +836,11 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
         if (a.chunk && !split_round) {
             const int per = (total + 7) >> 3;
             const int q = w >> 3;
-            if (q >= per) return;
+            if (q >= per) return false;
             w = (w & 7) * per + q;
             chunked = true;
         }
-        if (w >= total) return;
+        if (w >= total) return false;
         // Heavy and light blocks dealt evenly over the launch.  With a.num_heavy the block list
         // holds the blocks of multi-block experts first (their workgroups are bound by the matrix
         // cores and leave HBM mostly alone), then the single-block experts (bound by the weight
@@ -884,7 +894,7 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
     // The schedule entry is read once: the look-ups (block count, entry, expert offsets, for
     // the gate+up projection the source row) are dependent loads in front of the block's first
     // weight and tile loads, each worth several hundred nanoseconds of a ~100 us block.
-    if (tile >= *a.num_blocks) return;
+    if (tile >= *a.num_blocks) return false;
     const int bm = a.M < 256 ? a.M : 256;              // rows per schedule entry
     const int e = blist[2 * tile];
     const int r_in = blist[2 * tile + 1];
@@ -894,7 +904,11 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
     int ti = r_in / bm;                                // which of them this workgroup is
     // see below; a.even: 0 never, 1 experts of up to three row tiles, 2 those while the launch is at most two rounds, 3 always
     const bool even = a.even == 3 || (n <= 3 && (a.even == 1 || (a.even == 2 && total <= 2 * a.slots)));
-    if (a.sib && !halves && !chunked && !dealt && n >= 2) {
+    // An expert whose span reaches into a split last round keeps the plain order in all of its
+    // workgroups, the halves and the whole tiles before them alike: the two orders number the
+    // positions of a span differently, so one span must use one of them throughout.
+    const bool in_split = (tile - ti + n) * a.n_tiles_n > split_from;
+    if (a.sib && !in_split && !chunked && !dealt && n >= 2) {
         auto body = [](int rows) { const int c = (rows + 31) >> 5; return c > 7 ? 8 : c; };
         // tiles that run the same body as the first one (all of them when the rows are dealt evenly)
         const int nf = (even || body(n_e - (n - 1) * bm) == body(bm)) ? n : n - 1;
@@ -946,11 +960,29 @@ __global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(cons
         rows = per;
     }
     rows = (n_e - row_in) < rows ? (n_e - row_in) : rows;
-    if (rows <= 0) return;                              // (n >= 8 only: the rounding can empty the last entry)
-    t.e = e;
-    t.row0 = seg0 + row_in;
-    t.rows = rows;
-    t.n_e = n_e;
+    if (rows <= 0) return false;                            // (n >= 8 only: the rounding can empty the last entry)
+    m.e = e;
+    m.row0 = seg0 + row_in;
+    m.rows = rows;
+    m.n_e = n_e;
+    m.nt = nt;
+    m.halves = halves;
+    return true;
+}
+
+// The kernel: what to work on from mixed_assign, the regime from the expert's rows, the body from the block's.
+template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
+__global__ __launch_bounds__(kThreads, HALF ? 2 : 1) void tile_kernel_mixed(const GemmArgs a) {
+    extern __shared__ __attribute__((aligned(1024))) uint16_t xs[];
+    MixedWork m;
+    if (!mixed_assign<IB, GATEUP>(a, (int)blockIdx.x, m)) return;
+    Tile t;
+    const int nt = m.nt;
+    const bool halves = m.halves;
+    t.e = m.e;
+    t.row0 = m.row0;
+    t.rows = m.rows;
+    t.n_e = m.n_e;
     GemmArgs b = a;
     // A short last tile of a multi-tile expert runs through k several times faster than its
     // siblings and shares nothing with them in time: it streams the panel like a single-block
@@ -1112,17 +1144,12 @@ hipError_t launch_tile(const GemmArgs& a, int max_blocks, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
-hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
+// Launch order switches, feature-tile count and grid of a tile_kernel_mixed launch (host arithmetic
+// only; `cus` = CUs of the device).  Returns the grid size.
+template <int IB, bool GATEUP, bool WNT>
+inline long long mixed_launch_shape(GemmArgs& args, int max_blocks, int cus) {
     constexpr int BN = 4 * IB * 32;
-    constexpr int lds = 4 * (HALF ? 4 : 8) * 32 * 128;   // the DMA ring: XD+1 = 4 buffers of 256 (128) rows x 128 bytes
-    auto kern = tile_kernel_mixed<IB, GATEUP, PACKED, WNT, HALF>;
-    // once per process and kernel: not allowed while a stream is being captured into a graph
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (attr != hipSuccess) return attr;
-    GemmArgs args = a;
-    args.n_tiles_n = (a.N + BN - 1) / BN;
+    args.n_tiles_n = (args.N + BN - 1) / BN;
     args.rot_mul = rot_steps(false);
     // Test knobs (see moe_internal.hpp) can override the three launch-order choices; -1 = the rule.
     args.sib = knob(kKnobSideBySide) >= 0 ? knob(kKnobSideBySide) : 1;
@@ -1134,15 +1161,28 @@ hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
     long long grid = ((long long)max_blocks * args.n_tiles_n + 7) / 8 * 8;   // whole eighths for the per-XCD chunking
     args.slots = 0;
     if constexpr (IB == 2 && !GATEUP) {
-        static const int cus = [] {
-            int dev = 0, n = 0;
-            if (hipGetDevice(&dev) != hipSuccess) return 0;
-            if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-            return n;
-        }();
         args.slots = cus;
         grid += cus / 2;     // a split last round has up to slots/2 extra workgroups
     }
+    return grid;
+}
+
+template <int IB, bool GATEUP, bool PACKED, bool WNT, bool HALF = false>
+hipError_t launch_tile_mixed(const GemmArgs& a, int max_blocks, hipStream_t s) {
+    constexpr int lds = 4 * (HALF ? 4 : 8) * 32 * 128;   // the DMA ring: XD+1 = 4 buffers of 256 (128) rows x 128 bytes
+    auto kern = tile_kernel_mixed<IB, GATEUP, PACKED, WNT, HALF>;
+    // once per process and kernel: not allowed while a stream is being captured into a graph
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (attr != hipSuccess) return attr;
+    static const int cus = [] {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        return n;
+    }();
+    GemmArgs args = a;
+    const long long grid = mixed_launch_shape<IB, GATEUP, WNT>(args, max_blocks, cus);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(kThreads), lds, s, args);
     return hipGetLastError();
 }

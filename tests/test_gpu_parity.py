@@ -383,6 +383,45 @@ def test_multi_tile_experts_all_rows(G, knobs, name):
         _all_rows_against_oracle(G, layer, ref, other)
 
 
+def test_expert_span_across_a_split_last_round(G, knobs):
+    """Down projection with two weight blocks per wavefront whose launch is one full round of the
+    CUs plus a last round at most half full (that round's tiles are split into 128-feature halves),
+    with an expert of seven row tiles whose span lies partly in the full round and partly in the
+    split one: 3 experts x ~1667 rows, d = 4096 -> 21 blocks x 16 tiles = 336 workgroups on 256 CUs,
+    spans [0,112) [112,224) [224,336).  Every element against the oracle, and bit-equal with the
+    side-by-side order off; the same launch is enumerated on the host as well."""
+    import torch
+    import paper_2605_23911_amd as moe
+    import paper_2605_23911_amd.binding as B
+    s = mi.MoEShape("straddle", 5000, 4096, 1024, 3, 1, mi.GATE_SOFTMAX)
+    layer = G.Layer(s, seed=13, skew=0.0)
+    ref = _oracle_full(layer)
+    cfg = layer.cfg()
+    assert moe.tile_m(cfg) == 256 and moe.ffn_kernel_name(cfg, 1, True).startswith("tile_kernel_mixed<2, false, true, false")
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    tiles = [(int(c) + 255) // 256 * (s.d // 256) for c in ref["counts"]]
+    total, ends = sum(tiles), np.cumsum(tiles)
+    assert cus < total <= cus + cus // 2, "the launch must be one full round and a last round at most half full"
+    assert cus not in ends and min(tiles) >= 2 * (s.d // 256), "a multi-tile expert's span must cross the round boundary"
+    offsets = ref["offsets"].astype(np.int32)
+    blocks = np.array(orc.block_schedule(offsets, 256), dtype=np.int32)
+    work = B.map_launch(False, 2, False, s.d, 256, offsets, blocks, cus=cus, slack_blocks=moe.max_blocks(cfg, 256) - len(blocks))
+    cover = np.zeros((s.R, s.d // 128), dtype=np.int16)
+    for has, e, row0, rows, nt, width in work:
+        if has:
+            cover[row0:row0 + rows, nt * width:(nt + 1) * width] += 1
+    assert cover.min() == 1 and cover.max() == 1 and (work[:, 5] == 1).sum() == 2 * (total - cus)
+    knobs(B.KNOB_SHORT_NT, 0)    # every tile walks k from step 0: bit-for-bit comparisons below
+    _say("straddle: default launch order, all rows")
+    out = G.run_forward(layer)
+    _all_rows_against_oracle(G, layer, ref, out)
+    knobs(B.KNOB_SIDE_BY_SIDE, 0)
+    _say("straddle: tile-major order")
+    plain = G.run_forward(layer)
+    for key in ("h", "y_perm", "y"):
+        assert np.array_equal(out[key], plain[key]), key
+
+
 @pytest.mark.parametrize("shape,skew", [(("ragged", 333, 192, 320, 7, 3), 2.0), (("wide", 700, 512, 256, 16, 4), 1.0),
                                         (("five_tiles", 1100, 2048, 1024, 2, 2), 0.0), (("e256", 300, 256, 192, 256, 8), 0.0)])
 def test_combine_folded_into_the_down_projection(G, shape, skew):
