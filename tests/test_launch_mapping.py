@@ -126,3 +126,29 @@ def test_default_order_of_a_known_launch(L):
     assert sorted(live) == sorted([(0, 0, 160, 0, 1), (0, 0, 160, 1, 1), (0, 160, 140, 0, 1), (0, 160, 140, 1, 1),
                                    (1, 300, 40, 0, 1), (1, 300, 40, 1, 1)])
     assert len(work) == 8 and [int(w[0]) for w in work] == [1] * 6 + [0] * 2
+
+
+@pytest.mark.parametrize("name,T", [("mixtral", 512), ("mixtral", 2048), ("mixtral", 4096), ("qwen2moe", 512), ("qwen2moe", 4096),
+                                    ("dsv3", 512), ("dsv3", 4096), ("mixtral22", 4096)])
+def test_contract_shapes_in_their_default_launch_order(L, name, T):
+    """The benchmark contract's shapes at their real widths, expert sizes drawn from a multinomial
+    over rank^-s popularities (s = 0, 1, 2), in the order and with the kernel forms the selection
+    rules pick at that size (tile height from moe_tile_m; every kernel form is enumerated, the
+    rules' choice among them)."""
+    import moe_inputs as mi
+    s = mi.PRESETS[name].with_T(T)
+    cfg = moe.MoEConfig.of(s.T, s.d, s.F, s.E, s.k, s.gating)
+    M = moe.tile_m(cfg)
+    rng = np.random.default_rng(7)
+    for skew in (0.0, 1.0, 2.0):
+        p = np.arange(1, s.E + 1, dtype=np.float64) ** -skew
+        counts = rng.multinomial(s.R, rng.permutation(p / p.sum()))
+        counts = np.minimum(counts, s.T)          # an expert holds a token at most once
+        offsets, blocks, mix, num_heavy = _schedule(counts, M)
+        slack = moe.max_blocks(cfg, M) - len(blocks)
+        assert slack >= 0
+        for gateup, ib, wnt in _KERNELS:
+            N = s.F if gateup else s.d
+            mixed = mix if (not gateup and ib == 2 and not wnt) else None
+            work = B.map_launch(gateup, ib, wnt, N, M, offsets, blocks, mixed, num_heavy, cus=256, slack_blocks=slack)
+            _check_cover(work, offsets, counts, N, M, (name, T, skew, gateup, ib, wnt))
