@@ -157,7 +157,7 @@ def _cell(G, preset, T, skew, n_y):
 # (preset, T, skew, tokens whose y is compared).  Ordered so that each shape's weights are
 # generated once.
 _CELLS = (
-    [("mixtral", T, 0.0, 2) for T in (1, 16, 64, 256, 512, 4096)]
+    [("mixtral", T, 0.0, 2) for T in (1, 16, 64, 256, 512, 1024, 2048, 4096)]   # 1024, 2048: the T sweep's other rows
     + [("qwen2moe", T, 0.0, 4) for T in (16, 128)]
     + [("qwen2moe", T, s, 4) for T in (512, 4096) for s in (0.0, 1.0, 1.5, 2.0)]
     + [("dsv3", 64, 0.0, 2)]
