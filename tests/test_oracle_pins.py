@@ -262,6 +262,21 @@ def test_whole_layer_against_pure_python(gating, use_bias):
     assert np.abs(out["y"]).max() > 1e-3
 
 
+def test_whole_layer_against_pure_python_square_matrices():
+    """E = d = F: every weight matrix is square, the one case in which a transposed operand
+    multiplies without a shape error."""
+    T, n, k = 4, 6, 3
+    x, wr, wg, wu, wd = _rand_layer(T, n, n, n, seed=17)
+    out = orc.moe_forward(x, wr, None, _provider(wg, wu, wd), k, orc.GATE_SOFTMAX_RENORM)
+    ys, picks = _python_layer(_val(x).tolist(), _val(wr).tolist(), _val(wg).tolist(), _val(wu).tolist(),
+                              _val(wd).tolist(), None, k, orc.GATE_SOFTMAX_RENORM)
+    for t in range(T):
+        assert out["topk_idx"][t].tolist() == picks[t][0]
+        assert np.abs(out["topk_w"][t] - np.array(picks[t][1])).max() < 1e-14
+    assert np.abs(out["y"] - np.array(ys)).max() < 1e-12
+    assert np.abs(out["y"]).max() > 1e-3
+
+
 def test_layer_invariants():
     T, d, F, E, k = 12, 32, 40, 6, 3
     x, wr, wg, wu, wd = _rand_layer(T, d, F, E, seed=20)
@@ -298,15 +313,17 @@ def test_layer_invariants():
     assert np.abs(inj["y"] - base["y"]).max() < 1e-13
 
 
-def test_down_projection_is_not_transposed():
-    # d != F and a W_down with a single non-zero entry: y[:, c] = h[:, f] * w
-    T, d, F = 3, 8, 16
+@pytest.mark.parametrize("d,F,c,f", [(8, 16, 5, 11), (16, 16, 5, 11)])
+def test_down_projection_is_not_transposed(d, F, c, f):
+    # a W_down [d, F] with a single non-zero entry at (c, f): y[:, c] = h[:, f] * w.  With d != F a
+    # transposed operand cannot even be multiplied; with d == F it can, silently, hence both shapes.
+    T = 3
     x, wr, wg, wu, wd = _rand_layer(T, d, F, 1, seed=22)
     wd0 = np.zeros((1, d, F), np.float32)
-    wd0[0, 5, 11] = 3.0
+    wd0[0, c, f] = 3.0
     out = orc.moe_forward(x, wr, None, _provider(wg, wu, _bits(wd0)), 1, orc.GATE_SOFTMAX, keep_h=True)
     want = np.zeros((T, d))
-    want[:, 5] = 3.0 * out["h"][:, 0, 11]
+    want[:, c] = 3.0 * out["h"][:, 0, f]
     assert np.array_equal(out["y"], want)
 
 
