@@ -140,3 +140,12 @@ def test_entry_points_refuse_cpu_tensors(L):
     t = torch.zeros(8, dtype=torch.int32)
     with pytest.raises((ValueError, RuntimeError)):
         moe.moe_combine(c, t, t, t, t)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching a device."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in (res.stdout + res.stderr)
